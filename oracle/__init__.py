@@ -1,0 +1,20 @@
+"""CPU oracle for the FlashOmni attention path -- TEST INFRASTRUCTURE ONLY.
+
+A plain fp64 restatement of what Algorithm 1 computes (two-pass softmax over the kept
+key blocks, raw copy for cached query blocks) plus the symbol packing of Section 3.3.
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package; the product package never does, and the two share no code.
+
+Parity status: every function here is pinned by the CPU test-suite (printed packing
+example, textbook dense attention, closed forms, brute force).  Numerical parity with
+the authors' own kernel is unpinned: the paper prints no attention outputs.
+"""
+from .reference import (  # noqa: F401
+    pack_symbols,
+    unpack_symbols,
+    sparse_attention,
+    sparse_attention_blocks,
+    count_pairs,
+    sparsity,
+    num_threads,
+)

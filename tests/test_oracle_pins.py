@@ -1,0 +1,272 @@
+"""Pins of the CPU oracle against what the paper prints and what the mathematics fixes.
+
+None of these tests touch the GPU library.  Each one is chosen so that a plausible slip
+in the oracle (dropped scale, wrong bit order, transposed operand, normalising over all
+keys instead of kept keys, off-by-one in the block index, ...) fails at least one.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_25401_amd import synth
+from helpers import bits_to_f64, brute_force_attention, computed_row_mask
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "symbol_packing.txt")
+
+
+def _golden_rows():
+    rows = []
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            kind, bits, vals = [t.strip() for t in line.split("|")]
+            rows.append((kind, [int(t) for t in bits.split()], [int(t) for t in vals.split()]))
+    return rows
+
+
+# ---------------------------------------------------------------- symbol packing (Section 3.3)
+def test_packing_printed_example():
+    rows = [r for r in _golden_rows() if r[0] == "printed"]
+    assert rows, "golden file lost the printed example"
+    for _, bits, vals in rows:
+        assert oracle.pack_symbols(np.array(bits)).tolist() == vals
+
+
+def test_packing_printed_bytes_roundtrip():
+    for kind, bits, vals in _golden_rows():
+        if kind != "roundtrip":
+            continue
+        assert oracle.unpack_symbols(np.array(vals, dtype=np.uint8), len(bits)).tolist() == bits
+        assert oracle.pack_symbols(np.array(bits), flat=True).tolist() == vals
+
+
+def test_packing_roundtrip_and_padding():
+    rng = np.random.default_rng(0)
+    for n in (1, 7, 8, 9, 36, 258):
+        bits = (rng.random((3, 5, n)) < 0.5).astype(np.uint8)
+        packed = oracle.pack_symbols(bits)
+        assert packed.shape == (3, 5, (n + 7) // 8)
+        assert (oracle.unpack_symbols(packed, n) == bits).all()
+        # padding bits are zero
+        full = oracle.unpack_symbols(packed, packed.shape[-1] * 8)
+        assert (full[..., n:] == 0).all()
+        # against the library bit packer
+        assert (packed == np.packbits(bits, axis=-1, bitorder="big")).all()
+
+
+def test_flat_and_row_padded_layouts_agree_when_rows_are_whole_bytes():
+    rng = np.random.default_rng(1)
+    for Tkv in (8, 16):
+        bits = (rng.random((4, Tkv)) < 0.5).astype(np.uint8)
+        assert (oracle.pack_symbols(bits).reshape(-1) == oracle.pack_symbols(bits, flat=True)).all()
+
+
+# ---------------------------------------------------------------- dense special case (Section 3.1)
+@pytest.mark.parametrize("shape", [(1, 2, 128, 64, 64, 64), (2, 3, 192, 32, 64, 32), (1, 1, 96, 128, 32, 48)])
+@pytest.mark.parametrize("explicit_ones", [False, True])
+def test_dense_special_case_is_textbook_attention(shape, explicit_ones):
+    B, H, L, D, bq, bk = shape
+    w = synth.random_case(11, B, H, L, D, bq, bk, keep=1.0)
+    mask = oracle.pack_symbols(np.ones((B, H, L // bq, L // bk), dtype=np.uint8)) if explicit_ones else None
+    O, Ob = oracle.sparse_attention(w.Q, w.K, w.V, None, mask, None, bq, bk)
+    q, k, v = (torch.from_numpy(bits_to_f64(t)) for t in (w.Q, w.K, w.V))
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v).numpy()
+    assert np.abs(O - ref).max() < 1e-12
+    # the bf16 copy is the rounding of the fp64 result
+    assert np.abs(bits_to_f64(Ob) - O).max() <= np.abs(O).max() * 2.0 ** -8
+
+
+# ---------------------------------------------------------------- brute force on tiny inputs
+@pytest.mark.parametrize("case", [
+    dict(B=1, H=2, L=128, D=64, bq=64, bk=64, keep=0.5, cached=0.0),
+    dict(B=2, H=2, L=144, D=16, bq=48, bk=16, keep=0.4, cached=0.3),   # Tkv = 9: ragged last byte
+    dict(B=1, H=3, L=160, D=8, bq=16, bk=32, keep=0.3, cached=0.2),    # bq < bk
+    dict(B=1, H=1, L=320, D=32, bq=32, bk=16, keep=0.2, cached=0.0),   # Tkv = 20: three bytes
+])
+def test_against_element_level_brute_force(case):
+    w = synth.random_case(100 + case["L"], case["B"], case["H"], case["L"], case["D"], case["bq"], case["bk"],
+                          keep=case["keep"], cached_frac=case["cached"], force_diagonal=False)
+    mask = oracle.pack_symbols(w.M_s)
+    O, _ = oracle.sparse_attention(w.Q, w.K, w.V, w.cache_flags, mask, w.O_cache, case["bq"], case["bk"])
+    ref = brute_force_attention(w.Q, w.K, w.V, w.M_s, w.cache_flags, case["bq"], case["bk"])
+    rows = computed_row_mask(w.cache_flags, w.B, w.H, w.L, w.block_q)
+    assert rows.any()
+    assert np.abs(O[rows] - ref[rows]).max() < 1e-12
+
+
+def test_config_tiny_against_brute_force():
+    w = synth.config_tiny()
+    O, _ = oracle.sparse_attention(w.Q, w.K, w.V, None, oracle.pack_symbols(w.M_s), None, w.block_q, w.block_k)
+    ref = brute_force_attention(w.Q, w.K, w.V, w.M_s, None, w.block_q, w.block_k)
+    assert np.abs(O - ref).max() < 1e-12
+
+
+# ---------------------------------------------------------------- closed forms
+def test_zero_queries_give_mean_of_kept_values_and_expose_visited_tiles():
+    """Q = 0: all scores are 0, so each output row is the plain mean of the kept V rows.
+    With V[k, c] = 1 when key block of k is c, column c of the output is 1/|J_i| exactly
+    when block c is kept: the visited set is read off the output."""
+    B, H, L, D, bq, bk = 1, 2, 288, 16, 32, 24      # Tkv = 12 <= D
+    Tq, Tkv = L // bq, L // bk
+    rng = np.random.default_rng(5)
+    M = (rng.random((B, H, Tq, Tkv)) < 0.4).astype(np.uint8)
+    M[0, 0, 0, :] = 0
+    M[0, 0, 0, Tkv - 1] = 1            # only the last block
+    M[0, 1, 3, :] = 1                  # full row
+    M[0, 1, 4, :] = 0                  # empty row -> zeros
+    Vf = np.zeros((B, H, L, D), dtype=np.float32)
+    for k in range(L):
+        Vf[:, :, k, k // bk] = 1.0
+    Q = np.zeros((B, H, L, D), dtype=np.uint16)
+    K = synth.normal_bf16(rng, (B, H, L, D))
+    V = synth.f32_to_bf16_bits(Vf)
+    O, _ = oracle.sparse_attention(Q, K, V, None, oracle.pack_symbols(M), None, bq, bk)
+    for h in range(H):
+        for i in range(Tq):
+            n = int(M[0, h, i].sum())
+            expect = np.zeros(D)
+            if n:
+                expect[:Tkv] = M[0, h, i] / n
+            blk = O[0, h, i * bq:(i + 1) * bq]
+            assert np.abs(blk - expect[None]).max() < 1e-15, (h, i)
+
+
+def test_constant_value_columns_are_reproduced_for_any_mask():
+    """Softmax weights sum to one over the kept keys only: V constant per column => O equals it."""
+    w = synth.random_case(21, 1, 2, 256, 32, 32, 64, keep=0.3)
+    const = np.linspace(-2, 2, w.D).astype(np.float32)
+    V = synth.f32_to_bf16_bits(np.broadcast_to(const, w.V.shape).copy())
+    O, _ = oracle.sparse_attention(w.Q, w.K, V, None, oracle.pack_symbols(w.M_s), None, w.block_q, w.block_k)
+    expect = bits_to_f64(V)[0, 0, 0]
+    assert np.abs(O - expect).max() < 1e-14
+
+
+def test_rows_are_convex_combinations_of_kept_values():
+    w = synth.random_case(22, 1, 2, 256, 16, 64, 32, keep=0.25)
+    O, _ = oracle.sparse_attention(w.Q, w.K, w.V, None, oracle.pack_symbols(w.M_s), None, w.block_q, w.block_k)
+    Vf = bits_to_f64(w.V)
+    for h in range(w.H):
+        for i in range(w.Tq):
+            keys = np.flatnonzero(np.repeat(w.M_s[0, h, i], w.block_k))
+            lo, hi = Vf[0, h, keys].min(axis=0), Vf[0, h, keys].max(axis=0)
+            blk = O[0, h, i * w.block_q:(i + 1) * w.block_q]
+            assert (blk >= lo - 1e-12).all() and (blk <= hi + 1e-12).all()
+
+
+def test_single_kept_tile_is_dense_attention_on_that_tile():
+    w = synth.random_case(23, 1, 2, 256, 32, 64, 32, keep=0.0, force_diagonal=False)
+    rng = np.random.default_rng(7)
+    M = np.zeros((1, 2, w.Tq, w.Tkv), dtype=np.uint8)
+    pick = rng.integers(0, w.Tkv, size=(2, w.Tq))
+    for h in range(2):
+        for i in range(w.Tq):
+            M[0, h, i, pick[h, i]] = 1
+    O, _ = oracle.sparse_attention(w.Q, w.K, w.V, None, oracle.pack_symbols(M), None, w.block_q, w.block_k)
+    Qf, Kf, Vf = (torch.from_numpy(bits_to_f64(t)) for t in (w.Q, w.K, w.V))
+    for h in range(2):
+        for i in range(w.Tq):
+            j = pick[h, i]
+            q = Qf[0, h, i * 64:(i + 1) * 64][None, None]
+            k = Kf[0, h, j * 32:(j + 1) * 32][None, None]
+            v = Vf[0, h, j * 32:(j + 1) * 32][None, None]
+            ref = torch.nn.functional.scaled_dot_product_attention(q, k, v)[0, 0].numpy()
+            assert np.abs(O[0, h, i * 64:(i + 1) * 64] - ref).max() < 1e-12
+
+
+def test_key_block_order_is_free():
+    """Permuting key/value blocks together with their mask columns leaves O unchanged."""
+    w = synth.random_case(24, 1, 2, 320, 16, 64, 32, keep=0.4)
+    perm = np.random.default_rng(3).permutation(w.Tkv)
+    def blocks(x):
+        return x.reshape(w.B, w.H, w.Tkv, w.block_k, w.D)[:, :, perm].reshape(x.shape)
+    O1, _ = oracle.sparse_attention(w.Q, w.K, w.V, None, oracle.pack_symbols(w.M_s), None, w.block_q, w.block_k)
+    O2, _ = oracle.sparse_attention(w.Q, blocks(w.K), blocks(w.V), None,
+                                    oracle.pack_symbols(w.M_s[..., perm]), None, w.block_q, w.block_k)
+    assert np.abs(O1 - O2).max() < 1e-12
+
+
+def test_empty_mask_row_is_zero():
+    w = synth.random_case(25, 1, 1, 128, 16, 32, 32, keep=0.5)
+    M = w.M_s.copy()
+    M[0, 0, 2, :] = 0
+    O, Ob = oracle.sparse_attention(w.Q, w.K, w.V, None, oracle.pack_symbols(M), None, 32, 32)
+    assert (O[0, 0, 64:96] == 0).all() and (Ob[0, 0, 64:96] == 0).all()
+    assert np.abs(O[0, 0, :64]).max() > 0
+
+
+# ---------------------------------------------------------------- cache-then-reuse branch
+def test_cached_blocks_are_raw_copies_and_ignore_their_mask_rows():
+    w = synth.random_case(26, 2, 2, 192, 16, 32, 64, keep=0.5, cached_frac=0.5)
+    assert w.cache_flags.any() and (w.cache_flags == 0).any()
+    Oc = w.O_cache.copy()
+    Oc[0, 0, :4, :4] = np.array([0x7FC1, 0xFF80, 0x8000, 0x0001], dtype=np.uint16)   # NaN payload, -inf, -0, denormal
+    flags = w.cache_flags.copy()
+    flags[0, 0, 0] = 1
+    mask = oracle.pack_symbols(w.M_s)
+    O, Ob = oracle.sparse_attention(w.Q, w.K, w.V, flags, mask, Oc, 32, 64)
+    cached_rows = ~computed_row_mask(flags, w.B, w.H, w.L, 32)
+    assert (Ob[cached_rows] == Oc[cached_rows]).all()
+    # scrambling the mask rows of cached blocks changes nothing
+    M2 = w.M_s.copy()
+    M2[flags != 0] ^= 1
+    O2, Ob2 = oracle.sparse_attention(w.Q, w.K, w.V, flags, oracle.pack_symbols(M2), Oc, 32, 64)
+    assert (Ob2 == Ob).all()
+    # computed rows do not depend on the cached tensor
+    ref = brute_force_attention(w.Q, w.K, w.V, w.M_s, flags, 32, 64)
+    assert np.abs(O[~cached_rows] - ref[~cached_rows]).max() < 1e-12
+
+
+def test_cached_blocks_untouched_without_cache_tensor():
+    w = synth.random_case(27, 1, 2, 128, 16, 32, 32, keep=0.5, cached_frac=0.5, with_cache_tensor=False)
+    sentinel = np.full(w.Q.shape, 0x4242, dtype=np.uint16)
+    _, Ob = oracle.sparse_attention(w.Q, w.K, w.V, w.cache_flags, oracle.pack_symbols(w.M_s), None, 32, 32,
+                                    O_init_bits=sentinel)
+    cached_rows = ~computed_row_mask(w.cache_flags, w.B, w.H, w.L, 32)
+    assert cached_rows.any()
+    assert (Ob[cached_rows] == 0x4242).all()
+    assert (Ob[~cached_rows] != 0x4242).any()
+
+
+def test_padding_bits_are_ignored():
+    w = synth.random_case(28, 1, 2, 144, 16, 48, 16, keep=0.4)      # Tkv = 9 -> 7 padding bits
+    mask = oracle.pack_symbols(w.M_s)
+    dirty = mask.copy()
+    dirty[..., -1] |= 0x7F
+    O1, _ = oracle.sparse_attention(w.Q, w.K, w.V, None, mask, None, 48, 16)
+    O2, _ = oracle.sparse_attention(w.Q, w.K, w.V, None, dirty, None, 48, 16)
+    assert (O1 == O2).all()
+
+
+# ---------------------------------------------------------------- block subset API and accounting
+def test_block_subset_matches_full_run():
+    w = synth.random_case(29, 2, 2, 192, 16, 32, 64, keep=0.5, cached_frac=0.3)
+    mask = oracle.pack_symbols(w.M_s)
+    O, Ob = oracle.sparse_attention(w.Q, w.K, w.V, w.cache_flags, mask, w.O_cache, 32, 64)
+    items = np.random.default_rng(2).permutation(w.B * w.H * w.Tq)[:9]
+    Os, Obs = oracle.sparse_attention_blocks(w.Q, w.K, w.V, w.cache_flags, mask, w.O_cache, 32, 64, items)
+    full = O.reshape(w.B * w.H * w.Tq, 32, w.D)
+    fullb = Ob.reshape(w.B * w.H * w.Tq, 32, w.D)
+    assert (Os == full[items]).all() and (Obs == fullb[items]).all()
+
+
+def test_pair_accounting_matches_plain_counting():
+    """Sparsity = skip / total over block pairs (Section 4.1)."""
+    w = synth.random_case(30, 2, 3, 432, 8, 48, 16, keep=0.35, cached_frac=0.4)
+    mask = oracle.pack_symbols(w.M_s)
+    kept, total = oracle.count_pairs(w.cache_flags, mask, w.B, w.H, w.L, 48, 16)
+    brute = 0
+    for b in range(w.B):
+        for h in range(w.H):
+            for i in range(w.Tq):
+                if not w.cache_flags[b, h, i]:
+                    brute += sum(int(x) for x in w.M_s[b, h, i])
+    assert kept == brute == w.kept_pairs()
+    assert total == w.B * w.H * w.Tq * w.Tkv == w.total_pairs()
+    assert oracle.sparsity(w.cache_flags, mask, w.B, w.H, w.L, 48, 16) == pytest.approx(1 - brute / total)
+    k2, _ = oracle.count_pairs(None, None, w.B, w.H, w.L, 48, 16)
+    assert k2 == total
