@@ -1,0 +1,120 @@
+/*
+ * sparse_attn.h -- C ABI of the MI355X (gfx950) FlashOmni attention library.
+ *
+ * The operation is the paper's Algorithm 1 ("FlashOmni Attention"): a FlashAttention-style
+ * fused QK^T -> online softmax -> PV pass over bf16 Q/K/V that is steered by two block
+ * level sparse symbols (Definitions 1 and 2, Section 3.3):
+ *   - a per (batch, head, query block) cache flag, the spatial-axis symbol S_c: a flagged
+ *     block is not computed, its output is reused from a cached output tensor
+ *     ("cache-then-reuse" with OP_reuse = identity, a bit-exact copy);
+ *   - a bit-packed per (batch, head, query block, key block) mask, the reduction-axis symbol
+ *     S_s: a pair whose bit is 0 is skipped, its K/V tile is never loaded, and the softmax
+ *     normalises over the kept key blocks only ("compute-on-demand").
+ *
+ * Conventions shared by every entry point
+ *   - Tensors Q, K, V, O_cache, O: bf16, shape [B, H, L, D], D fastest, fully contiguous,
+ *     16-byte aligned base.  Tq = L / block_q, Tkv = L / block_k.
+ *   - cache_flags: uint8 [B, H, Tq]; non-zero = reuse the block from O_cache.  Note the
+ *     polarity: the paper's logical mask M_c holds 0 for cached blocks, this flag holds 1.
+ *     NULL = no block is cached.
+ *   - kv_mask: uint8 [B, H, Tq, ceil(Tkv / 8)]; logical entry j of a row lives in byte j / 8
+ *     at bit 7 - j % 8 (most significant bit first, as the worked example of Section 3.3
+ *     [1,1,1,0] -> 0b11100000 = 224 fixes); 1 = compute the pair.  Every (b, h, i) row starts
+ *     on a byte boundary; bits past Tkv are ignored; rows of cached blocks are ignored.
+ *     NULL = every pair is kept (dense attention).
+ *   - A computed block whose mask row is empty is written as +0.0.
+ *   - Scores are scaled by 1 / sqrt(D) (Section 3.1).  Products run on bf16 MFMA with fp32
+ *     accumulation, the softmax weights are rounded to bf16 before the PV product, the result
+ *     is rounded to bf16 (nearest even).
+ *   - Supported shapes: D in {64, 128}; block_q, block_k in {64, 128}; L a multiple of both
+ *     block sizes; Tq <= 16384.
+ *   - "device" pointers are HIP device memory owned by the caller; the library never frees
+ *     or keeps them.  "host" pointers are ordinary host memory.
+ *   - Return value: 0 on success, a negative SPARSE_ATTN_ERR_* code otherwise; a message for
+ *     the last failure on the calling thread is available from sparse_attn_last_error().
+ *     Argument validation happens before any HIP call, and nothing is written on failure.
+ *   - There is no CPU fallback: without a usable HIP device the compute entry points fail
+ *     with SPARSE_ATTN_ERR_HIP.
+ */
+#ifndef SPARSE_ATTN_H
+#define SPARSE_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPARSE_ATTN_OK 0
+#define SPARSE_ATTN_ERR_INVALID (-1)     /* NULL pointer, non-positive size, L not a multiple of a block, O aliases an input */
+#define SPARSE_ATTN_ERR_UNSUPPORTED (-2) /* D or block size outside the supported set, Tq too large */
+#define SPARSE_ATTN_ERR_HIP (-3)         /* a HIP runtime call failed; see sparse_attn_last_error() */
+
+/*
+ * Algorithm 1 on the HIP null stream.
+ *   Q, K, V      device, bf16 [B,H,L,D], read only
+ *   cache_flags  device, uint8 [B,H,Tq] or NULL
+ *   kv_mask      device, uint8 [B,H,Tq,ceil(Tkv/8)] or NULL
+ *   O_cache      device, bf16 [B,H,L,D]; NULL or equal to O means the cached blocks of O are
+ *                already in place (Algorithm 1: "continue if O_i is already updated") and are
+ *                not touched
+ *   O            device, bf16 [B,H,L,D], written (computed blocks always; cached blocks only
+ *                when O_cache is a different tensor).  Must not overlap Q, K or V.
+ * The call is asynchronous with respect to the host.  It uses a per (device, stream) scratch
+ * buffer that the library allocates on first use and grows when needed (hipMalloc); calls that
+ * overlap in time on one stream object are not supported.
+ */
+int sparse_attn_fwd(const void* Q, const void* K, const void* V,
+                    const uint8_t* cache_flags, const uint8_t* kv_mask,
+                    const void* O_cache, void* O,
+                    int B, int H, int L, int D, int block_q, int block_k);
+
+/* Same, enqueued on the caller's stream (a hipStream_t passed as void*; NULL = null stream). */
+int sparse_attn_fwd_stream(const void* Q, const void* K, const void* V,
+                           const uint8_t* cache_flags, const uint8_t* kv_mask,
+                           const void* O_cache, void* O,
+                           int B, int H, int L, int D, int block_q, int block_k,
+                           void* hip_stream);
+
+/*
+ * Measurement variant: same work as sparse_attn_fwd_stream, bracketed by HIP events on the
+ * given stream, synchronised before returning.  plan_ms (host, may be NULL) receives the
+ * duration of the symbol pre-pass (decode, count and ordering of work items), attn_ms (host,
+ * may be NULL) the duration of the attention kernel itself, both in milliseconds.
+ */
+int sparse_attn_fwd_timed(const void* Q, const void* K, const void* V,
+                          const uint8_t* cache_flags, const uint8_t* kv_mask,
+                          const void* O_cache, void* O,
+                          int B, int H, int L, int D, int block_q, int block_k,
+                          void* hip_stream, float* plan_ms, float* attn_ms);
+
+/* Bytes of device scratch one call of this shape uses (0 for invalid shapes). */
+size_t sparse_attn_workspace_bytes(int B, int H, int L, int block_q, int block_k);
+
+/*
+ * Pair accounting of Section 4.1 (Sparsity = skip / total over (Q_i K_j^T, P_ij V_j) pairs).
+ * cache_flags and kv_mask are HOST copies (either may be NULL, meaning as above).
+ * kept_pairs (host) receives the number of pairs that are computed, i.e. set mask bits of
+ * non-cached rows; total_pairs (host, may be NULL) receives B*H*Tq*Tkv.  Pure host code.
+ */
+int sparse_attn_count_kept(const uint8_t* cache_flags, const uint8_t* kv_mask,
+                           int B, int H, int L, int block_q, int block_k,
+                           unsigned long long* kept_pairs, unsigned long long* total_pairs);
+
+/*
+ * Symbol compression of Section 3.3 for the kv_mask argument.  logical (host): rows x Tkv
+ * bytes, each 0 or non-zero; packed (host): rows x ceil(Tkv/8) bytes, written.  Pure host code.
+ */
+int sparse_attn_pack_mask(const uint8_t* logical, long long rows, int Tkv, uint8_t* packed);
+
+/* Message for the last non-zero return on the calling thread ("" if none). Never NULL. */
+const char* sparse_attn_last_error(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int sparse_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSE_ATTN_H */

@@ -4,3 +4,15 @@ The product is the C-ABI library built from ``csrc/`` (declared in ``include/spa
 this package is the thin Python binding over it plus the seeded synthetic workloads.
 """
 from . import synth  # noqa: F401
+from .binding import (  # noqa: F401
+    SparseAttnError,
+    library_path,
+    load_library,
+    sparse_attn_fwd,
+    sparse_attn_fwd_timed,
+    sparse_attn_pack_mask,
+    sparse_attn_count_kept,
+    sparse_attn_workspace_bytes,
+    sparse_attn_version,
+    sparse_attn_last_error,
+)

@@ -1,0 +1,154 @@
+"""ctypes binding of the C-ABI in include/sparse_attn.h -- argument marshalling only.
+
+Every step of the attention path runs inside the HIP library; PyTorch is used for device
+memory and the current stream.  There is no fallback: if the library has not been built the
+calls raise.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsparse_attn_hip.so")
+_lib = None
+
+
+class SparseAttnError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"sparse_attn error {code}: {message}")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libsparse_attn_hip.so (built by paper_2509_25401_amd/build.py); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2509_25401_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32 = ctypes.c_void_p, ctypes.c_int
+    fwd_args = [vp] * 7 + [i32] * 6
+    lib.sparse_attn_fwd.argtypes = fwd_args
+    lib.sparse_attn_fwd.restype = i32
+    lib.sparse_attn_fwd_stream.argtypes = fwd_args + [vp]
+    lib.sparse_attn_fwd_stream.restype = i32
+    lib.sparse_attn_fwd_timed.argtypes = fwd_args + [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+    lib.sparse_attn_fwd_timed.restype = i32
+    lib.sparse_attn_workspace_bytes.argtypes = [i32] * 5
+    lib.sparse_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.sparse_attn_count_kept.argtypes = [vp, vp] + [i32] * 5 + [ctypes.POINTER(ctypes.c_ulonglong)] * 2
+    lib.sparse_attn_count_kept.restype = i32
+    lib.sparse_attn_pack_mask.argtypes = [vp, ctypes.c_longlong, i32, vp]
+    lib.sparse_attn_pack_mask.restype = i32
+    lib.sparse_attn_last_error.argtypes = []
+    lib.sparse_attn_last_error.restype = ctypes.c_char_p
+    lib.sparse_attn_version.argtypes = []
+    lib.sparse_attn_version.restype = i32
+    _lib = lib
+    return lib
+
+
+def sparse_attn_last_error() -> str:
+    return load_library().sparse_attn_last_error().decode()
+
+
+def sparse_attn_version() -> int:
+    return int(load_library().sparse_attn_version())
+
+
+def _raise(code):
+    raise SparseAttnError(code, sparse_attn_last_error())
+
+
+def _dev_ptr(t, name, allow_none=False):
+    if t is None:
+        if allow_none:
+            return None
+        raise ValueError(f"{name} must not be None")
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _fwd_args(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k):
+    B, H, L, D = Q.shape
+    for name, t in (("K", K), ("V", V), ("O", O)):
+        if tuple(t.shape) != (B, H, L, D):
+            raise ValueError(f"{name} must have the shape of Q")
+    return [_dev_ptr(Q, "Q"), _dev_ptr(K, "K"), _dev_ptr(V, "V"),
+            _dev_ptr(cache_flags, "cache_flags", True), _dev_ptr(kv_mask, "kv_mask", True),
+            _dev_ptr(O_cache, "O_cache", True), _dev_ptr(O, "O"),
+            int(B), int(H), int(L), int(D), int(block_q), int(block_k)]
+
+
+def sparse_attn_fwd(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k, stream=None):
+    """Algorithm 1 on device tensors (bf16 [B,H,L,D]); enqueued on `stream` (default: torch's current stream).
+
+    cache_flags: uint8 [B,H,Tq] or None; kv_mask: uint8 [B,H,Tq,ceil(Tkv/8)] (see sparse_attn_pack_mask) or None;
+    O_cache: bf16 [B,H,L,D], None or O itself (cached blocks already in place).  O is written in place.
+    """
+    args = _fwd_args(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k)
+    rc = load_library().sparse_attn_fwd_stream(*args, _stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
+    return O
+
+
+def sparse_attn_fwd_timed(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k, stream=None):
+    """Same work, timed with HIP events inside the library.  Returns (plan_ms, attn_ms)."""
+    args = _fwd_args(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k)
+    plan, attn = ctypes.c_float(0), ctypes.c_float(0)
+    rc = load_library().sparse_attn_fwd_timed(*args, _stream_ptr(stream), ctypes.byref(plan), ctypes.byref(attn))
+    if rc != 0:
+        _raise(rc)
+    return plan.value, attn.value
+
+
+def sparse_attn_workspace_bytes(B, H, L, block_q, block_k) -> int:
+    return int(load_library().sparse_attn_workspace_bytes(B, H, L, block_q, block_k))
+
+
+def sparse_attn_count_kept(cache_flags, kv_mask, B, H, L, block_q, block_k):
+    """(kept, total) pair counts from HOST numpy arrays (uint8), either may be None."""
+    def host(a):
+        if a is None:
+            return None, None
+        a = np.ascontiguousarray(a, dtype=np.uint8)
+        return a, a.ctypes.data_as(ctypes.c_void_p)
+    f, fp = host(cache_flags)
+    m, mp = host(kv_mask)
+    kept, total = ctypes.c_ulonglong(0), ctypes.c_ulonglong(0)
+    rc = load_library().sparse_attn_count_kept(fp, mp, B, H, L, block_q, block_k, ctypes.byref(kept), ctypes.byref(total))
+    if rc != 0:
+        _raise(rc)
+    return kept.value, total.value
+
+
+def sparse_attn_pack_mask(logical):
+    """Pack a HOST logical mask (numpy, last axis = key blocks, non-zero = keep) into kv_mask bytes."""
+    a = np.ascontiguousarray(logical)
+    a = (a != 0).astype(np.uint8)
+    Tkv = a.shape[-1]
+    rows = int(np.prod(a.shape[:-1])) if a.ndim > 1 else 1
+    out = np.empty(a.shape[:-1] + ((Tkv + 7) // 8,), dtype=np.uint8)
+    rc = load_library().sparse_attn_pack_mask(a.ctypes.data_as(ctypes.c_void_p), rows, Tkv,
+                                              out.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        _raise(rc)
+    return out

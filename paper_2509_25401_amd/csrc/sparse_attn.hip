@@ -1,0 +1,650 @@
+// FlashOmni attention (Algorithm 1 of the paper) for AMD MI355X / gfx950.
+//
+// Three kernels per call, all on the caller's stream:
+//   plan_rows   decodes the packed symbols of Section 3.3 once per (b,h,i) row into aligned
+//               32-bit words (bit j of the row = key block j, padding cleared) and counts the
+//               kept key blocks of every non-cached row;
+//   plan_order  orders the rows into a work list: heaviest rows first (16 count buckets), rows
+//               of one head adjacent inside a bucket so that concurrently running workgroups
+//               share that head's K/V in L2, cached rows (plain copies) last;
+//   attn        a persistent grid of workgroups pulls items from the list.  A compute item is
+//               one query block: Q lives in registers, the reduction-axis symbol is walked
+//               with scalar bit operations (find-first-set on the decoded words, no vector
+//               work), and only kept K/V tiles are streamed HBM -> LDS with direct-to-LDS
+//               loads, double buffered in 64-key sub-tiles.  S^T = K Q^T and O^T = V^T P^T run
+//               on v_mfma_f32_32x32x16_bf16, so each lane owns one query row: the row maximum
+//               needs a single half-wave exchange and the row sum none until the end.  A copy
+//               item moves one cached block O_cache -> O with 16-byte coalesced accesses.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <map>
+#include <mutex>
+#include <utility>
+
+#include "sparse_attn.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+#define LDS_PTR(T) T __attribute__((address_space(3)))*
+#define GLOBAL_PTR(T) T __attribute__((address_space(1)))*
+
+constexpr int kKeys = 64;             // keys per LDS sub-tile
+constexpr int kBuckets = 16;          // kept-count buckets of the work ordering
+constexpr int kMaxHeadGroups = 512;   // head groups per bucket in the ordering histogram
+constexpr int kMaxTq = 16384;
+constexpr unsigned kCopyFlag = 0x80000000u;
+constexpr int kOrderThreads = 1024;
+
+struct AttnParams {
+  const char* Q;
+  const char* K;
+  const char* V;
+  const char* O_cache;
+  char* O;
+  const uint32_t* words;   // [N][nw32] decoded symbol words
+  const uint32_t* order;   // [N] work list: row | kCopyFlag
+  uint32_t* counter;       // work queue head
+  int N;                   // B*H*Tq
+  int Tq;
+  int L;
+  int nw32;
+  int do_copy;             // 0: cached blocks are already in place
+  float scale_log2;        // log2(e) / sqrt(D)
+};
+
+// ---------------------------------------------------------------------------------------
+// Symbol pre-pass
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) plan_rows(const uint8_t* __restrict__ cache_flags,
+                                                 const uint8_t* __restrict__ kv_mask, int N, int Tkv,
+                                                 int row_bytes, int nw32, uint32_t* __restrict__ words,
+                                                 int32_t* __restrict__ keys) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= N) return;
+  const bool cached = cache_flags != nullptr && cache_flags[row] != 0;
+  int count = 0;
+  const uint8_t* src = kv_mask ? kv_mask + (size_t)row * row_bytes : nullptr;
+  for (int w = 0; w < nw32; ++w) {
+    uint32_t word = 0;
+    if (!cached) {
+      if (src) {
+        for (int b = 0; b < 4; ++b) {
+          const int byte = 4 * w + b;
+          if (byte < row_bytes) word |= (__brev((uint32_t)src[byte]) >> 24) << (8 * b);
+        }
+      } else {
+        word = 0xffffffffu;
+      }
+      const int valid = Tkv - 32 * w;   // >= 1 by construction of nw32
+      if (valid < 32) word &= (1u << valid) - 1u;
+    }
+    words[(size_t)row * nw32 + w] = word;
+    count += __popc(word);
+  }
+  keys[row] = cached ? -1 : count;
+}
+
+__device__ inline int order_bin(int key, int row, int Tq, int Tkv, int shift, int groups) {
+  const int bh = row / Tq;
+  const int major = key < 0 ? kBuckets : (kBuckets - 1) - (int)(((long long)key * kBuckets) / (Tkv + 1));
+  return major * groups + (bh >> shift);
+}
+
+__global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __restrict__ keys, int N, int Tq,
+                                                            int Tkv, int shift, int groups,
+                                                            uint32_t* __restrict__ order,
+                                                            uint32_t* __restrict__ counter) {
+  __shared__ uint32_t bins[(kBuckets + 1) * kMaxHeadGroups];
+  __shared__ uint32_t partial[kOrderThreads];
+  const int tid = threadIdx.x;
+  const int nbins = (kBuckets + 1) * groups;
+  for (int b = tid; b < nbins; b += kOrderThreads) bins[b] = 0;
+  __syncthreads();
+  for (int r = tid; r < N; r += kOrderThreads) atomicAdd(&bins[order_bin(keys[r], r, Tq, Tkv, shift, groups)], 1u);
+  __syncthreads();
+  // exclusive scan of bins: contiguous chunk per thread, then a scan over the chunk sums
+  const int chunk = (nbins + kOrderThreads - 1) / kOrderThreads;
+  const int lo = tid * chunk, hi = min(nbins, lo + chunk);
+  uint32_t sum = 0;
+  for (int b = lo; b < hi; ++b) sum += bins[b];
+  partial[tid] = sum;
+  __syncthreads();
+  for (int off = 1; off < kOrderThreads; off <<= 1) {
+    uint32_t add = tid >= off ? partial[tid - off] : 0u;
+    __syncthreads();
+    partial[tid] += add;
+    __syncthreads();
+  }
+  uint32_t run = partial[tid] - sum;
+  for (int b = lo; b < hi; ++b) {
+    const uint32_t c = bins[b];
+    bins[b] = run;
+    run += c;
+  }
+  __syncthreads();
+  for (int r = tid; r < N; r += kOrderThreads) {
+    const int key = keys[r];
+    const uint32_t pos = atomicAdd(&bins[order_bin(key, r, Tq, Tkv, shift, groups)], 1u);
+    order[pos] = (uint32_t)r | (key < 0 ? kCopyFlag : 0u);
+  }
+  if (tid == 0) *counter = 0u;
+}
+
+// ---------------------------------------------------------------------------------------
+// LDS layouts.  A sub-tile is kKeys rows of D bf16, row major, with the 16-byte chunks of a
+// row permuted by an XOR that depends on the row, so that (a) the 32 rows x 16 B that one
+// S^T operand read touches and (b) the 8 rows x 64 B that one transposed V read touches fall
+// into distinct banks.  A direct-to-LDS load writes 1 KiB of consecutive LDS per wave
+// instruction, so the permutation is applied to the global address each lane fetches.
+// ---------------------------------------------------------------------------------------
+template <int D>
+__device__ __forceinline__ int k_swizzle(int row) {
+  return D == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+template <int D>
+__device__ __forceinline__ int v_swizzle(int row) {
+  return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1);
+}
+
+__device__ __forceinline__ void wait_vmem() {
+  // s_waitcnt vmcnt(0) only: expcnt and lgkmcnt fields left at their maxima
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+}
+
+template <int D, int BQ, int BK>
+__global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
+  constexpr int NWAVES = BQ / 32;
+  constexpr int NT = NWAVES * 64;
+  constexpr int SUB = BK / kKeys;          // LDS sub-tiles per symbol bit
+  constexpr int CH = D / 8;                // 16-byte chunks per row
+  constexpr int ROWB = D * 2;              // bytes per row
+  constexpr int TILEB = kKeys * ROWB;      // bytes per K or V sub-tile
+  constexpr int NINST = TILEB / 1024;      // direct-to-LDS wave instructions per sub-tile
+  constexpr int ROWS_PER_INST = 1024 / ROWB;
+  constexpr int KS = D / 16;               // k-steps of the S^T product
+  constexpr int DB = D / 32;               // 32-row blocks of O^T
+  static_assert(NINST % NWAVES == 0, "sub-tile loads must split evenly over the waves");
+
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  char* const ldsK = smem;
+  char* const ldsV = smem + 2 * TILEB;
+  volatile int* const s_item = (volatile int*)(smem + 4 * TILEB);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31;    // query row inside the wave's 32-row slab / key row of an operand read
+  const int half = lane >> 5;   // which 8 of the 16 k-slots of an MFMA this lane feeds
+  const int i16 = lane & 15;
+  const int g4 = lane >> 4;
+  const float c = p.scale_log2;
+
+  for (;;) {
+    if (tid == 0) *s_item = (int)atomicAdd(p.counter, 1u);
+    __syncthreads();
+    const int n = __builtin_amdgcn_readfirstlane(*s_item);
+    if (n >= p.N) break;
+    const uint32_t entry = p.order[n];
+    const int row = (int)(entry & ~kCopyFlag);
+    const int bh = row / p.Tq;
+    const int iq = row - bh * p.Tq;
+    const size_t head_off = (size_t)bh * p.L * ROWB;
+    const size_t blk_off = head_off + (size_t)iq * BQ * ROWB;
+
+    if (entry & kCopyFlag) {
+      // cache-then-reuse: O_i <- cached O_i, bit exact
+      if (p.do_copy) {
+        const u32x4* src = (const u32x4*)(p.O_cache + blk_off);
+        u32x4* dst = (u32x4*)(p.O + blk_off);
+        constexpr int NV = BQ * ROWB / 16;
+#pragma unroll 4
+        for (int t = tid; t < NV; t += NT) dst[t] = src[t];
+      }
+      __syncthreads();
+      continue;
+    }
+
+    // ---- compute-on-demand ----
+    const char* Kh = p.K + head_off;
+    const char* Vh = p.V + head_off;
+    const uint32_t* wp = p.words + (size_t)row * p.nw32;
+
+    // Q fragment: B operand of S^T = K Q^T; lane holds query row l32, d = 16*ks + 8*half .. +7
+    bf16x8 qf[KS];
+    {
+      const char* qrow = p.Q + blk_off + (size_t)(wave * 32 + l32) * ROWB + half * 16;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qrow + ks * 32);
+    }
+
+    f32x16 o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
+    float m_run = -INFINITY;
+    float l_run = 0.f;   // per-lane partial row sum (this lane's half of the keys)
+
+    // scalar walk over the set bits of the decoded symbol row
+    int w_idx = 0;
+    uint32_t w_bits = p.nw32 > 0 ? wp[0] : 0u;
+    auto next_block = [&]() -> int {
+      while (w_bits == 0u) {
+        ++w_idx;
+        if (w_idx >= p.nw32) return -1;
+        w_bits = wp[w_idx];
+      }
+      const int b = __builtin_ctz(w_bits);
+      w_bits &= w_bits - 1u;
+      return 32 * w_idx + b;
+    };
+
+    auto issue_loads = [&](int j, int sub, int buf) {
+      const size_t tile_off = ((size_t)j * BK + (size_t)sub * kKeys) * ROWB;
+      const char* gK = Kh + tile_off;
+      const char* gV = Vh + tile_off;
+#pragma unroll
+      for (int t = 0; t < NINST / NWAVES; ++t) {
+        const int inst = wave + t * NWAVES;
+        const int r = inst * ROWS_PER_INST + lane / CH;
+        const int pch = lane % CH;
+        const int ck = pch ^ k_swizzle<D>(r);
+        const int cv = pch ^ v_swizzle<D>(r);
+        __builtin_amdgcn_global_load_lds((GLOBAL_PTR(const void))(gK + r * ROWB + ck * 16),
+                                         (LDS_PTR(void))(ldsK + buf * TILEB + inst * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((GLOBAL_PTR(const void))(gV + r * ROWB + cv * 16),
+                                         (LDS_PTR(void))(ldsV + buf * TILEB + inst * 1024), 16, 0, 0);
+      }
+    };
+
+    auto compute = [&](int buf) {
+      const char* kb = ldsK + buf * TILEB;
+      const char* vb = ldsV + buf * TILEB;
+      // S^T[key][query] for 64 keys: two 32x32 blocks
+      f32x16 s[2];
+#pragma unroll
+      for (int kb2 = 0; kb2 < 2; ++kb2) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[kb2][e] = 0.f;
+        const int r = 32 * kb2 + l32;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const int ch = (2 * ks + half) ^ k_swizzle<D>(r);
+          const bf16x8 a = *(const bf16x8*)(kb + r * ROWB + ch * 16);
+          s[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb2], 0, 0, 0);
+        }
+      }
+      // online softmax; this lane sees 32 of the 64 scores of its query row
+      float mx = s[0][0];
+#pragma unroll
+      for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb2][e]);
+      {
+        const unsigned bits = __builtin_bit_cast(unsigned, mx);
+        const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+        mx = fmaxf(__builtin_bit_cast(float, (unsigned)sw[0]), __builtin_bit_cast(float, (unsigned)sw[1]));
+      }
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+      const float mc = m_new * c;
+      m_run = m_new;
+      float psum = 0.f;
+#pragma unroll
+      for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][e], c, -mc));
+          s[kb2][e] = pv;
+          psum += pv;
+        }
+      l_run = l_run * alpha + psum;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+      // O^T += V^T P^T.  k-slot s of lane-half h maps to key 32*kb2 + 16*ksp + 8*(s/4) + 4*h + s%4,
+      // which is exactly the key order of the S^T accumulator registers 8*ksp .. 8*ksp+7.
+#pragma unroll
+      for (int kb2 = 0; kb2 < 2; ++kb2) {
+#pragma unroll
+        for (int ksp = 0; ksp < 2; ++ksp) {
+          bf16x8 pb;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) pb[e] = (__bf16)s[kb2][8 * ksp + e];
+          const int r1 = 32 * kb2 + 16 * ksp + 4 * (g4 >> 1) + (i16 >> 2);
+          const int r2 = r1 + 8;
+#pragma unroll
+          for (int db = 0; db < DB; ++db) {
+            const int ch = 4 * db + 2 * (g4 & 1) + ((i16 & 3) >> 1);
+            const int within = 8 * (i16 & 1);
+            const s16x4 t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (LDS_PTR(s16x4))(vb + r1 * ROWB + ((ch ^ v_swizzle<D>(r1)) * 16) + within));
+            const s16x4 t2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (LDS_PTR(s16x4))(vb + r2 * ROWB + ((ch ^ v_swizzle<D>(r2)) * 16) + within));
+            const s16x8 a16 = __builtin_shufflevector(t1, t2, 0, 1, 2, 3, 4, 5, 6, 7);
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a16), pb, o[db], 0, 0, 0);
+          }
+        }
+      }
+    };
+
+    int j = next_block();
+    int sub = 0;
+    int buf = 0;
+    if (j >= 0) issue_loads(j, 0, 0);
+    while (j >= 0) {
+      int nj = j, nsub = sub + 1;
+      if (nsub == SUB) {
+        nsub = 0;
+        nj = next_block();
+      }
+      wait_vmem();
+      __syncthreads();   // sub-tile `buf` has landed for every wave; the other buffer is free
+      if (nj >= 0) issue_loads(nj, nsub, buf ^ 1);
+      compute(buf);
+      j = nj;
+      sub = nsub;
+      buf ^= 1;
+    }
+
+    // O_i = diag(l)^-1 O_acc; both lane halves hold partial sums of the same row
+    {
+      const unsigned bits = __builtin_bit_cast(unsigned, l_run);
+      const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+      const float l_tot = __builtin_bit_cast(float, (unsigned)sw[0]) + __builtin_bit_cast(float, (unsigned)sw[1]);
+      const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+      char* orow = p.O + blk_off + (size_t)(wave * 32 + l32) * ROWB;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          // accumulator registers 4*q4 .. 4*q4+3 hold d = 32*db + 8*q4 + 4*half + 0..3
+          bf16x2 lo, hi;
+          lo[0] = (__bf16)(o[db][4 * q4 + 0] * inv);
+          lo[1] = (__bf16)(o[db][4 * q4 + 1] * inv);
+          hi[0] = (__bf16)(o[db][4 * q4 + 2] * inv);
+          hi[1] = (__bf16)(o[db][4 * q4 + 3] * inv);
+          u32x2 pk;
+          pk[0] = __builtin_bit_cast(unsigned, lo);
+          pk[1] = __builtin_bit_cast(unsigned, hi);
+          *(u32x2*)(orow + (32 * db + 8 * q4 + 4 * half) * 2) = pk;
+        }
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------------------
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                          \
+  do {                                                                                         \
+    hipError_t e_ = (expr);                                                                    \
+    if (e_ != hipSuccess) return fail(SPARSE_ATTN_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+struct Shape {
+  int B, H, L, D, bq, bk, Tq, Tkv, N, row_bytes, nw32;
+};
+
+int check_shape(int B, int H, int L, int D, int bq, int bk, bool need_d, Shape* s) {
+  if (B <= 0 || H <= 0 || L <= 0 || bq <= 0 || bk <= 0 || (need_d && D <= 0))
+    return fail(SPARSE_ATTN_ERR_INVALID, "sizes must be positive (B=%d H=%d L=%d D=%d block_q=%d block_k=%d)", B, H,
+                L, D, bq, bk);
+  if ((bq != 64 && bq != 128) || (bk != 64 && bk != 128))
+    return fail(SPARSE_ATTN_ERR_UNSUPPORTED, "block_q and block_k must be 64 or 128 (got %d, %d)", bq, bk);
+  if (need_d && D != 64 && D != 128) return fail(SPARSE_ATTN_ERR_UNSUPPORTED, "D must be 64 or 128 (got %d)", D);
+  if (L % bq || L % bk)
+    return fail(SPARSE_ATTN_ERR_INVALID, "L=%d must be a multiple of block_q=%d and block_k=%d", L, bq, bk);
+  const long long n = (long long)B * H * (L / bq);
+  if (L / bq > kMaxTq) return fail(SPARSE_ATTN_ERR_UNSUPPORTED, "Tq=%d exceeds %d", L / bq, kMaxTq);
+  if (n > 0x3fffffffLL) return fail(SPARSE_ATTN_ERR_UNSUPPORTED, "too many query blocks (%lld)", n);
+  s->B = B; s->H = H; s->L = L; s->D = D; s->bq = bq; s->bk = bk;
+  s->Tq = L / bq;
+  s->Tkv = L / bk;
+  s->N = (int)n;
+  s->row_bytes = (s->Tkv + 7) / 8;
+  s->nw32 = (s->Tkv + 31) / 32;
+  return 0;
+}
+
+// scratch layout: [counter (256 B)] [order N u32] [keys N i32] [words N*nw32 u32]
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+size_t workspace_bytes(const Shape& s) {
+  return 256 + align256((size_t)s.N * 4) * 2 + align256((size_t)s.N * s.nw32 * 4);
+}
+
+struct Scratch {
+  void* ptr = nullptr;
+  size_t bytes = 0;
+};
+std::mutex g_mu;
+std::map<std::pair<int, void*>, Scratch> g_scratch;
+
+int get_scratch(size_t need, hipStream_t stream, void** out) {
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> lock(g_mu);
+  Scratch& sc = g_scratch[std::make_pair(dev, (void*)stream)];
+  if (sc.bytes < need) {
+    if (sc.ptr) {
+      HIP_TRY(hipStreamSynchronize(stream));
+      HIP_TRY(hipFree(sc.ptr));
+      sc.ptr = nullptr;
+      sc.bytes = 0;
+    }
+    const size_t want = need + need / 2;
+    HIP_TRY(hipMalloc(&sc.ptr, want));
+    sc.bytes = want;
+  }
+  *out = sc.ptr;
+  return 0;
+}
+
+bool overlaps(const void* a, const void* b, size_t bytes) {
+  const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + bytes && y < x + bytes;
+}
+
+template <int D, int BQ, int BK>
+int launch_attn(const AttnParams& p, int grid, hipStream_t stream) {
+  constexpr size_t lds = 4 * (size_t)kKeys * D * 2 + 16;
+  static bool attr_set = false;
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute((const void*)attn_kernel<D, BQ, BK>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((attn_kernel<D, BQ, BK>), dim3(grid), dim3(BQ * 2), lds, stream, p);
+  HIP_TRY(hipGetLastError());
+  return 0;
+}
+
+int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags, const uint8_t* kv_mask,
+        const void* O_cache, void* O, int B, int H, int L, int D, int bq, int bk, hipStream_t stream, float* plan_ms,
+        float* attn_ms, bool timed) {
+  Shape s;
+  if (int rc = check_shape(B, H, L, D, bq, bk, true, &s)) return rc;
+  if (!Q || !K || !V || !O) return fail(SPARSE_ATTN_ERR_INVALID, "Q, K, V and O must not be NULL");
+  const size_t tensor_bytes = (size_t)B * H * L * D * 2;
+  if (overlaps(O, Q, tensor_bytes) || overlaps(O, K, tensor_bytes) || overlaps(O, V, tensor_bytes))
+    return fail(SPARSE_ATTN_ERR_INVALID, "O must not overlap Q, K or V");
+  if (O_cache && O_cache != O && overlaps(O, O_cache, tensor_bytes))
+    return fail(SPARSE_ATTN_ERR_INVALID, "O_cache must be O itself or must not overlap O");
+  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O | (uintptr_t)O_cache) & 15)
+    return fail(SPARSE_ATTN_ERR_INVALID, "tensor base pointers must be 16-byte aligned");
+
+  void* ws = nullptr;
+  if (int rc = get_scratch(workspace_bytes(s), stream, &ws)) return rc;
+  char* base = (char*)ws;
+  uint32_t* counter = (uint32_t*)base;
+  uint32_t* order = (uint32_t*)(base + 256);
+  int32_t* keys = (int32_t*)(base + 256 + align256((size_t)s.N * 4));
+  uint32_t* words = (uint32_t*)(base + 256 + 2 * align256((size_t)s.N * 4));
+
+  int dev = 0, cus = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+
+  hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+  if (timed) {
+    for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
+    HIP_TRY(hipEventRecord(ev[0], stream));
+  }
+
+  const int BH = B * H;
+  int shift = 0;
+  while (((BH - 1) >> shift) + 1 > kMaxHeadGroups) ++shift;
+  const int groups = ((BH - 1) >> shift) + 1;
+  hipLaunchKernelGGL(plan_rows, dim3((s.N + 255) / 256), dim3(256), 0, stream, cache_flags, kv_mask, s.N, s.Tkv,
+                     s.row_bytes, s.nw32, words, keys);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(plan_order, dim3(1), dim3(kOrderThreads), 0, stream, keys, s.N, s.Tq, s.Tkv, shift, groups,
+                     order, counter);
+  HIP_TRY(hipGetLastError());
+  if (timed) HIP_TRY(hipEventRecord(ev[1], stream));
+
+  AttnParams p;
+  p.Q = (const char*)Q;
+  p.K = (const char*)K;
+  p.V = (const char*)V;
+  p.O_cache = (const char*)O_cache;
+  p.O = (char*)O;
+  p.words = words;
+  p.order = order;
+  p.counter = counter;
+  p.N = s.N;
+  p.Tq = s.Tq;
+  p.L = L;
+  p.nw32 = s.nw32;
+  p.do_copy = (O_cache != nullptr && O_cache != O) ? 1 : 0;
+  p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
+  const int grid = s.N < 2 * cus ? s.N : 2 * cus;
+
+  int rc = 0;
+  if (D == 128 && bq == 128 && bk == 128) rc = launch_attn<128, 128, 128>(p, grid, stream);
+  else if (D == 128 && bq == 128 && bk == 64) rc = launch_attn<128, 128, 64>(p, grid, stream);
+  else if (D == 128 && bq == 64 && bk == 128) rc = launch_attn<128, 64, 128>(p, grid, stream);
+  else if (D == 128 && bq == 64 && bk == 64) rc = launch_attn<128, 64, 64>(p, grid, stream);
+  else if (D == 64 && bq == 128 && bk == 128) rc = launch_attn<64, 128, 128>(p, grid, stream);
+  else if (D == 64 && bq == 128 && bk == 64) rc = launch_attn<64, 128, 64>(p, grid, stream);
+  else if (D == 64 && bq == 64 && bk == 128) rc = launch_attn<64, 64, 128>(p, grid, stream);
+  else rc = launch_attn<64, 64, 64>(p, grid, stream);
+  if (rc) return rc;
+
+  if (timed) {
+    HIP_TRY(hipEventRecord(ev[2], stream));
+    HIP_TRY(hipEventSynchronize(ev[2]));
+    float a = 0.f, b = 0.f;
+    HIP_TRY(hipEventElapsedTime(&a, ev[0], ev[1]));
+    HIP_TRY(hipEventElapsedTime(&b, ev[1], ev[2]));
+    if (plan_ms) *plan_ms = a;
+    if (attn_ms) *attn_ms = b;
+    for (auto& e : ev) HIP_TRY(hipEventDestroy(e));
+  }
+  return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sparse_attn_fwd(const void* Q, const void* K, const void* V, const uint8_t* cache_flags, const uint8_t* kv_mask,
+                    const void* O_cache, void* O, int B, int H, int L, int D, int block_q, int block_k) {
+  return run(Q, K, V, cache_flags, kv_mask, O_cache, O, B, H, L, D, block_q, block_k, nullptr, nullptr, nullptr,
+             false);
+}
+
+int sparse_attn_fwd_stream(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
+                           const uint8_t* kv_mask, const void* O_cache, void* O, int B, int H, int L, int D,
+                           int block_q, int block_k, void* hip_stream) {
+  return run(Q, K, V, cache_flags, kv_mask, O_cache, O, B, H, L, D, block_q, block_k, (hipStream_t)hip_stream,
+             nullptr, nullptr, false);
+}
+
+int sparse_attn_fwd_timed(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
+                          const uint8_t* kv_mask, const void* O_cache, void* O, int B, int H, int L, int D,
+                          int block_q, int block_k, void* hip_stream, float* plan_ms, float* attn_ms) {
+  return run(Q, K, V, cache_flags, kv_mask, O_cache, O, B, H, L, D, block_q, block_k, (hipStream_t)hip_stream,
+             plan_ms, attn_ms, true);
+}
+
+size_t sparse_attn_workspace_bytes(int B, int H, int L, int block_q, int block_k) {
+  Shape s;
+  if (check_shape(B, H, L, 0, block_q, block_k, false, &s)) return 0;
+  return workspace_bytes(s);
+}
+
+int sparse_attn_count_kept(const uint8_t* cache_flags, const uint8_t* kv_mask, int B, int H, int L, int block_q,
+                           int block_k, unsigned long long* kept_pairs, unsigned long long* total_pairs) {
+  Shape s;
+  if (int rc = check_shape(B, H, L, 0, block_q, block_k, false, &s)) return rc;
+  if (!kept_pairs) return fail(SPARSE_ATTN_ERR_INVALID, "kept_pairs must not be NULL");
+  unsigned long long kept = 0;
+  for (int row = 0; row < s.N; ++row) {
+    if (cache_flags && cache_flags[row]) continue;
+    if (!kv_mask) {
+      kept += (unsigned long long)s.Tkv;
+      continue;
+    }
+    const uint8_t* r = kv_mask + (size_t)row * s.row_bytes;
+    for (int byte = 0; byte < s.row_bytes; ++byte) {
+      unsigned v = r[byte];
+      const int valid = s.Tkv - 8 * byte;
+      if (valid < 8) v &= (0xffu << (8 - valid)) & 0xffu;
+      kept += (unsigned long long)__builtin_popcount(v);
+    }
+  }
+  *kept_pairs = kept;
+  if (total_pairs) *total_pairs = (unsigned long long)s.N * (unsigned long long)s.Tkv;
+  return 0;
+}
+
+int sparse_attn_pack_mask(const uint8_t* logical, long long rows, int Tkv, uint8_t* packed) {
+  if (!logical || !packed || rows < 0 || Tkv <= 0)
+    return fail(SPARSE_ATTN_ERR_INVALID, "pack_mask: bad arguments (rows=%lld Tkv=%d)", rows, Tkv);
+  const int row_bytes = (Tkv + 7) / 8;
+  for (long long r = 0; r < rows; ++r) {
+    const uint8_t* src = logical + (size_t)r * Tkv;
+    uint8_t* dst = packed + (size_t)r * row_bytes;
+    for (int byte = 0; byte < row_bytes; ++byte) {
+      unsigned v = 0;
+      for (int t = 0; t < 8; ++t) {
+        const int j = 8 * byte + t;
+        if (j < Tkv && src[j]) v |= 0x80u >> t;
+      }
+      dst[byte] = (uint8_t)v;
+    }
+  }
+  return 0;
+}
+
+const char* sparse_attn_last_error(void) { return g_err; }
+
+int sparse_attn_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+"""Host-side checks of the C-ABI library: exported symbols, argument validation (which runs
+before any HIP call, so no GPU is needed) and the pure-host helpers against the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2509_25401_amd as pkg
+from paper_2509_25401_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b(sparse_attn_\w+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pkg.load_library()
+    names = _declared_functions()
+    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and len(names) >= 8
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
+    assert pkg.sparse_attn_version() >= 100
+
+
+FAKE = ctypes.c_void_p(0x10000)   # never dereferenced: every call below fails validation first
+
+
+def _fwd(B=1, H=1, L=128, D=128, bq=128, bk=128, Q=FAKE, K=FAKE, V=FAKE, O=ctypes.c_void_p(0x90000000)):
+    return pkg.load_library().sparse_attn_fwd(Q, K, V, None, None, None, O, B, H, L, D, bq, bk)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(B=0), -1), (dict(H=-1), -1), (dict(L=0), -1), (dict(D=0), -1),
+    (dict(L=192), -1),                 # not a multiple of the 128 blocks
+    (dict(L=192, bq=64, bk=128), -1),
+    (dict(D=96), -2), (dict(D=256), -2),
+    (dict(bq=32), -2), (dict(bk=256), -2), (dict(bq=0), -1),
+    (dict(Q=None), -1), (dict(K=None), -1), (dict(V=None), -1), (dict(O=None), -1),
+    (dict(O=FAKE), -1),                # O aliases Q
+    (dict(O=ctypes.c_void_p(0x10000 + 64)), -1),   # O overlaps Q
+    (dict(Q=ctypes.c_void_p(0x10008)), -1),        # misaligned
+    (dict(L=64 * 20000, bq=64, bk=64), -2),        # Tq beyond the supported maximum
+])
+def test_argument_validation_precedes_any_device_work(kw, code):
+    assert _fwd(**kw) == code
+    assert pkg.sparse_attn_last_error() != ""
+
+
+def test_workspace_bytes():
+    assert pkg.sparse_attn_workspace_bytes(1, 24, 33024, 128, 128) >= 24 * 258 * (4 + 4 + 9 * 4)
+    assert pkg.sparse_attn_workspace_bytes(1, 24, 33024, 128, 128) < 1 << 20
+    assert pkg.sparse_attn_workspace_bytes(1, 1, 100, 128, 128) == 0
+    assert pkg.sparse_attn_workspace_bytes(1, 1, 128, 32, 128) == 0
+
+
+def test_pack_mask_matches_printed_example_and_oracle_packer():
+    assert pkg.sparse_attn_pack_mask(np.array([1, 1, 1, 0])).tolist() == [224]   # Section 3.3 worked example
+    rng = np.random.default_rng(3)
+    for Tkv in (1, 7, 8, 9, 36, 258):
+        M = (rng.random((2, 3, 5, Tkv)) < 0.5).astype(np.uint8)
+        assert (pkg.sparse_attn_pack_mask(M) == oracle.pack_symbols(M)).all()
+
+
+def test_count_kept_matches_oracle_accounting():
+    w = synth.random_case(40, 2, 3, 1152, 8, 128, 64, keep=0.35, cached_frac=0.4)
+    mask = pkg.sparse_attn_pack_mask(w.M_s)
+    dirty = mask.copy()
+    dirty[..., -1] |= 0x3F      # Tkv = 18: the last byte has 6 padding bits
+    for m in (mask, dirty):
+        assert pkg.sparse_attn_count_kept(w.cache_flags, m, w.B, w.H, w.L, 128, 64) == \
+            oracle.count_pairs(w.cache_flags, mask, w.B, w.H, w.L, 128, 64) == (w.kept_pairs(), w.total_pairs())
+    assert pkg.sparse_attn_count_kept(None, None, w.B, w.H, w.L, 128, 64) == (w.total_pairs(), w.total_pairs())
+    with pytest.raises(pkg.SparseAttnError):
+        pkg.sparse_attn_count_kept(None, None, 1, 1, 100, 128, 64)
+
+
+def test_workload_recipes_hit_their_keep_ratios():
+    w2 = synth.config_image_skip()
+    assert abs(w2.kept_pairs() / w2.total_pairs() - 0.5) < 0.01
+    assert (w2.M_s[..., :4] == 1).all() and all(w2.M_s[0, 0, i, i] for i in range(w2.Tq))
+    w3 = synth.config_image_cache_skip()
+    assert (w3.cache_flags.sum(axis=-1) == 18).all() and (w3.cache_flags[..., :4] == 0).all()
+    rows = w3.M_s[w3.cache_flags == 0]
+    assert abs(rows.mean() - 0.3) < 0.01
