@@ -89,6 +89,17 @@ int sparse_attn_fwd_timed(const void* Q, const void* K, const void* V,
                           int B, int H, int L, int D, int block_q, int block_k,
                           void* hip_stream, float* plan_ms, float* attn_ms);
 
+/*
+ * Live kernel timing for benchmarks.  Between sparse_attn_profile_begin(max_calls) and
+ * sparse_attn_profile_end(), each of the first max_calls calls of sparse_attn_fwd /
+ * sparse_attn_fwd_stream records three HIP events on its own stream (start, after the symbol
+ * pre-pass, end) and does not synchronise.  sparse_attn_profile_end() waits for the recorded
+ * calls and returns their number and the summed durations in milliseconds of the pre-pass and
+ * of the attention kernel (host pointers, each may be NULL).  One profile at a time per process.
+ */
+int sparse_attn_profile_begin(int max_calls);
+int sparse_attn_profile_end(int* calls, double* plan_ms_total, double* attn_ms_total);
+
 /* Bytes of device scratch one call of this shape uses (0 for invalid shapes). */
 size_t sparse_attn_workspace_bytes(int B, int H, int L, int block_q, int block_k);
 

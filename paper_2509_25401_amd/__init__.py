@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     load_library,
     sparse_attn_fwd,
     sparse_attn_fwd_timed,
+    sparse_attn_profile_begin,
+    sparse_attn_profile_end,
     sparse_attn_pack_mask,
     sparse_attn_count_kept,
     sparse_attn_workspace_bytes,

@@ -48,6 +48,10 @@ def load_library():
     lib.sparse_attn_count_kept.restype = i32
     lib.sparse_attn_pack_mask.argtypes = [vp, ctypes.c_longlong, i32, vp]
     lib.sparse_attn_pack_mask.restype = i32
+    lib.sparse_attn_profile_begin.argtypes = [i32]
+    lib.sparse_attn_profile_begin.restype = i32
+    lib.sparse_attn_profile_end.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.sparse_attn_profile_end.restype = i32
     lib.sparse_attn_last_error.argtypes = []
     lib.sparse_attn_last_error.restype = ctypes.c_char_p
     lib.sparse_attn_version.argtypes = []
@@ -118,6 +122,21 @@ def sparse_attn_fwd_timed(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, bl
     if rc != 0:
         _raise(rc)
     return plan.value, attn.value
+
+
+def sparse_attn_profile_begin(max_calls: int) -> None:
+    rc = load_library().sparse_attn_profile_begin(int(max_calls))
+    if rc != 0:
+        _raise(rc)
+
+
+def sparse_attn_profile_end():
+    """Returns (calls, plan_ms_total, attn_ms_total) of the calls recorded since profile_begin."""
+    calls, plan, attn = ctypes.c_int(0), ctypes.c_double(0), ctypes.c_double(0)
+    rc = load_library().sparse_attn_profile_end(ctypes.byref(calls), ctypes.byref(plan), ctypes.byref(attn))
+    if rc != 0:
+        _raise(rc)
+    return calls.value, plan.value, attn.value
 
 
 def sparse_attn_workspace_bytes(B, H, L, block_q, block_k) -> int:

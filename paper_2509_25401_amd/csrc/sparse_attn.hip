@@ -465,6 +465,16 @@ int get_scratch(size_t need, hipStream_t stream, void** out) {
   return 0;
 }
 
+// Optional per-call event recording (sparse_attn_profile_begin/end): three events per call,
+// recorded on the call's stream without any synchronisation.
+struct Profile {
+  bool on = false;
+  int capacity = 0;
+  int calls = 0;
+  hipEvent_t* ev = nullptr;   // 3 per call: start, after the pre-pass, end
+};
+Profile g_prof;
+
 bool overlaps(const void* a, const void* b, size_t bytes) {
   const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
   return x < y + bytes && y < x + bytes;
@@ -511,10 +521,18 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
   HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
 
   hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+  bool record = timed;
   if (timed) {
     for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
-    HIP_TRY(hipEventRecord(ev[0], stream));
+  } else {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (g_prof.on && g_prof.calls < g_prof.capacity) {
+      for (int t = 0; t < 3; ++t) ev[t] = g_prof.ev[3 * g_prof.calls + t];
+      ++g_prof.calls;
+      record = true;
+    }
   }
+  if (record) HIP_TRY(hipEventRecord(ev[0], stream));
 
   const int BH = B * H;
   int shift = 0;
@@ -526,7 +544,7 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
   hipLaunchKernelGGL(plan_order, dim3(1), dim3(kOrderThreads), 0, stream, keys, s.N, s.Tq, s.Tkv, shift, groups,
                      order, counter);
   HIP_TRY(hipGetLastError());
-  if (timed) HIP_TRY(hipEventRecord(ev[1], stream));
+  if (record) HIP_TRY(hipEventRecord(ev[1], stream));
 
   AttnParams p;
   p.Q = (const char*)Q;
@@ -556,8 +574,8 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
   else rc = launch_attn<64, 64, 64>(p, grid, stream);
   if (rc) return rc;
 
+  if (record) HIP_TRY(hipEventRecord(ev[2], stream));
   if (timed) {
-    HIP_TRY(hipEventRecord(ev[2], stream));
     HIP_TRY(hipEventSynchronize(ev[2]));
     float a = 0.f, b = 0.f;
     HIP_TRY(hipEventElapsedTime(&a, ev[0], ev[1]));
@@ -641,6 +659,49 @@ int sparse_attn_pack_mask(const uint8_t* logical, long long rows, int Tkv, uint8
     }
   }
   return 0;
+}
+
+int sparse_attn_profile_begin(int max_calls) {
+  if (max_calls <= 0 || max_calls > (1 << 20)) return fail(SPARSE_ATTN_ERR_INVALID, "profile_begin: bad max_calls %d", max_calls);
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (g_prof.on) return fail(SPARSE_ATTN_ERR_INVALID, "profile_begin: a profile is already open");
+  g_prof.ev = new hipEvent_t[3 * (size_t)max_calls];
+  for (int t = 0; t < 3 * max_calls; ++t) {
+    hipError_t e = hipEventCreate(&g_prof.ev[t]);
+    if (e != hipSuccess) {
+      for (int u = 0; u < t; ++u) (void)hipEventDestroy(g_prof.ev[u]);
+      delete[] g_prof.ev;
+      g_prof.ev = nullptr;
+      return fail(SPARSE_ATTN_ERR_HIP, "hipEventCreate failed: %s", hipGetErrorString(e));
+    }
+  }
+  g_prof.capacity = max_calls;
+  g_prof.calls = 0;
+  g_prof.on = true;
+  return 0;
+}
+
+int sparse_attn_profile_end(int* calls, double* plan_ms_total, double* attn_ms_total) {
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (!g_prof.on) return fail(SPARSE_ATTN_ERR_INVALID, "profile_end: no profile is open");
+  int rc = 0;
+  double plan = 0.0, attn = 0.0;
+  for (int c = 0; c < g_prof.calls && rc == 0; ++c) {
+    hipError_t e = hipEventSynchronize(g_prof.ev[3 * c + 2]);
+    float a = 0.f, b = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&a, g_prof.ev[3 * c], g_prof.ev[3 * c + 1]);
+    if (e == hipSuccess) e = hipEventElapsedTime(&b, g_prof.ev[3 * c + 1], g_prof.ev[3 * c + 2]);
+    if (e != hipSuccess) rc = fail(SPARSE_ATTN_ERR_HIP, "profile_end: %s", hipGetErrorString(e));
+    plan += a;
+    attn += b;
+  }
+  for (int t = 0; t < 3 * g_prof.capacity; ++t) (void)hipEventDestroy(g_prof.ev[t]);
+  delete[] g_prof.ev;
+  if (calls) *calls = g_prof.calls;
+  if (plan_ms_total) *plan_ms_total = plan;
+  if (attn_ms_total) *attn_ms_total = attn;
+  g_prof = Profile();
+  return rc;
 }
 
 const char* sparse_attn_last_error(void) { return g_err; }
