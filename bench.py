@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the dense run, the sweep and config 4")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-blocks", type=int, default=256, help="query blocks in the oracle's timed sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--heads", type=int, default=24, help="heads (24 = the named workload; fewer only for quick checks)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -98,6 +100,14 @@ def main():
         log(f"{label}: {ms:.3f} ms/step (plan {res['plan_ms']:.3f} + attn {res['attn_ms']:.3f}), keep {res['keep']:.4f}, "
             f"{res['eff_tflops']:.1f} TFLOP/s effective")
         return res
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        log("copy calibration: one 1 GiB device-to-device copy dispatched")
 
     head = run_case(w.M_s, None, None, args.steps, args.warmup, f"headline keep={args.keep:g}")
 

@@ -43,10 +43,20 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 
 constexpr int kKeys = 64;             // keys per LDS sub-tile
 constexpr int kBuckets = 16;          // kept-count buckets of the work ordering
-constexpr int kMaxHeadGroups = 512;   // head groups per bucket in the ordering histogram
+constexpr int kXcds = 8;               // accelerator dies (XCDs) of the MI355X, each with its own L2
+constexpr int kMaxHeadGroups = 64;    // head groups per (XCD, bucket) in the ordering histogram
 constexpr int kMaxTq = 16384;
 constexpr unsigned kCopyFlag = 0x80000000u;
+constexpr int kHwRegXccId = (3 << 11) | 20;   // s_getreg operand: 4 bits at offset 0 of hardware register 20 (XCC_ID)
 constexpr int kOrderThreads = 1024;
+#ifndef SA_RESCALE_LOG2
+#define SA_RESCALE_LOG2 8.0f
+#endif
+#ifndef SA_MFMA_PRIO
+#define SA_MFMA_PRIO 1
+#endif
+constexpr int kMfmaPrio = SA_MFMA_PRIO;            // wave priority while it feeds the matrix pipe
+constexpr float kRescaleLog2 = SA_RESCALE_LOG2;   // how far a score may exceed the exponent's reference
 
 struct AttnParams {
   const char* Q;
@@ -56,9 +66,10 @@ struct AttnParams {
   char* O;
   const uint32_t* words;   // [N][nw32] decoded symbol words
   const uint32_t* order;   // [N] work list: row | kCopyFlag
-  uint32_t* counter;       // work queue head
+  uint32_t* queues;        // kXcds queue heads, then kXcds queue ends
   int N;                   // B*H*Tq
   int Tq;
+  int Tkv;
   int L;
   int nw32;
   int do_copy;             // 0: cached blocks are already in place
@@ -97,27 +108,32 @@ __global__ void __launch_bounds__(256) plan_rows(const uint8_t* __restrict__ cac
   keys[row] = cached ? -1 : count;
 }
 
+// Work list order: one queue per XCD (head bh belongs to XCD bh % kXcds, so the workgroups of
+// an XCD stream the K/V of one head at a time through that XCD's L2); inside a queue the
+// heaviest rows first (kBuckets kept-count buckets, longest-processing-time-first), rows of one
+// head adjacent inside a bucket, cached rows (plain copies) last.
 __device__ inline int order_bin(int key, int row, int Tq, int Tkv, int shift, int groups) {
   const int bh = row / Tq;
   const int major = key < 0 ? kBuckets : (kBuckets - 1) - (int)(((long long)key * kBuckets) / (Tkv + 1));
-  return major * groups + (bh >> shift);
+  return ((bh % kXcds) * (kBuckets + 1) + major) * groups + ((bh / kXcds) >> shift);
 }
 
 __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __restrict__ keys, int N, int Tq,
                                                             int Tkv, int shift, int groups,
                                                             uint32_t* __restrict__ order,
-                                                            uint32_t* __restrict__ counter) {
-  __shared__ uint32_t bins[(kBuckets + 1) * kMaxHeadGroups];
+                                                            uint32_t* __restrict__ queues) {
+  __shared__ uint32_t bins[kXcds * (kBuckets + 1) * kMaxHeadGroups];
   __shared__ uint32_t partial[kOrderThreads];
   const int tid = threadIdx.x;
-  const int nbins = (kBuckets + 1) * groups;
+  const int per_xcd = (kBuckets + 1) * groups;
+  const int nbins = kXcds * per_xcd;
   for (int b = tid; b < nbins; b += kOrderThreads) bins[b] = 0;
   __syncthreads();
   for (int r = tid; r < N; r += kOrderThreads) atomicAdd(&bins[order_bin(keys[r], r, Tq, Tkv, shift, groups)], 1u);
   __syncthreads();
   // exclusive scan of bins: contiguous chunk per thread, then a scan over the chunk sums
   const int chunk = (nbins + kOrderThreads - 1) / kOrderThreads;
-  const int lo = tid * chunk, hi = min(nbins, lo + chunk);
+  const int lo = min(nbins, tid * chunk), hi = min(nbins, lo + chunk);
   uint32_t sum = 0;
   for (int b = lo; b < hi; ++b) sum += bins[b];
   partial[tid] = sum;
@@ -135,12 +151,18 @@ __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __res
     run += c;
   }
   __syncthreads();
+  if (tid < kXcds) {
+    const uint32_t begin = bins[tid * per_xcd];
+    queues[tid] = begin;                                    // queue head
+    if (tid > 0) queues[kXcds + tid - 1] = begin;           // previous queue's end
+    if (tid == kXcds - 1) queues[2 * kXcds - 1] = (uint32_t)N;
+  }
+  __syncthreads();
   for (int r = tid; r < N; r += kOrderThreads) {
     const int key = keys[r];
     const uint32_t pos = atomicAdd(&bins[order_bin(key, r, Tq, Tkv, shift, groups)], 1u);
     order[pos] = (uint32_t)r | (key < 0 ? kCopyFlag : 0u);
   }
-  if (tid == 0) *counter = 0u;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -159,13 +181,35 @@ __device__ __forceinline__ int v_swizzle(int row) {
   return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1);
 }
 
+// Direct-to-LDS load: every lane fetches 16 bytes from gbase (wave-uniform) + lane_off, the wave's
+// 1 KiB lands at consecutive LDS addresses starting at the wave-uniform `lds_addr`.  Written as
+// inline assembly so that the compiler does not serialise later LDS reads of the OTHER buffer
+// behind these loads (it cannot tell the two buffers apart); the kernel waits for them itself
+// (wait_vmem + barrier) before the buffer is read.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void load_to_lds_16B(const char* gbase, unsigned lane_off, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(lane_off), "s"(gbase)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
 __device__ __forceinline__ void wait_vmem() {
   // s_waitcnt vmcnt(0) only: expcnt and lgkmcnt fields left at their maxima
   __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
+#ifdef SA_DEBUG_CLOCKS
+__device__ unsigned long long g_dbg_clocks[3 * 1024];
+#endif
+
 template <int D, int BQ, int BK>
 __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
+#ifdef SA_DEBUG_CLOCKS
+  const unsigned long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
+#endif
   constexpr int NWAVES = BQ / 32;
   constexpr int NT = NWAVES * 64;
   constexpr int SUB = BK / kKeys;          // LDS sub-tiles per symbol bit
@@ -173,15 +217,20 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
   constexpr int ROWB = D * 2;              // bytes per row
   constexpr int TILEB = kKeys * ROWB;      // bytes per K or V sub-tile
   constexpr int NINST = TILEB / 1024;      // direct-to-LDS wave instructions per sub-tile
+  constexpr int NLOAD = NINST / NWAVES;    // of which this wave issues
   constexpr int ROWS_PER_INST = 1024 / ROWB;
   constexpr int KS = D / 16;               // k-steps of the S^T product
   constexpr int DB = D / 32;               // 32-row blocks of O^T
+  constexpr int NQK = 2 * KS;              // MFMAs of S^T per sub-tile
+  constexpr int NPV = 4 * DB;              // MFMAs of O^T per sub-tile
+  constexpr int kPre = 4;                  // operand reads run this many MFMAs ahead
   static_assert(NINST % NWAVES == 0, "sub-tile loads must split evenly over the waves");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  char* const ldsK = smem;
+  char* const ldsK = smem;                 // two K sub-tiles, then two V sub-tiles
   char* const ldsV = smem + 2 * TILEB;
   volatile int* const s_item = (volatile int*)(smem + 4 * TILEB);
+  const unsigned lds_base = (unsigned)(uintptr_t)(LDS_PTR(char))smem;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -192,11 +241,49 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
   const int g4 = lane >> 4;
   const float c = p.scale_log2;
 
+  // Per-lane offsets, the same for every item.
+  unsigned k_goff[NLOAD], v_goff[NLOAD];   // global byte offsets inside a sub-tile (swizzle applied to the source)
+#pragma unroll
+  for (int t = 0; t < NLOAD; ++t) {
+    const int r = (wave + t * NWAVES) * ROWS_PER_INST + lane / CH;
+    const int pch = lane % CH;
+    k_goff[t] = (unsigned)(r * ROWB + ((pch ^ k_swizzle<D>(r)) * 16));
+    v_goff[t] = (unsigned)(r * ROWB + ((pch ^ v_swizzle<D>(r)) * 16));
+  }
+  int k_off[KS];     // S^T operand (K rows): LDS byte offset of k-step ks inside this lane's key row
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_off[ks] = l32 * ROWB + (((2 * ks + half) ^ k_swizzle<D>(l32)) * 16);
+  int v_off[DB];     // O^T operand (V transposed): LDS byte offset of d-block db for this lane
+  {
+    const int r = 4 * (g4 >> 1) + (i16 >> 2);   // key row inside an 8-row group; rows +8, +16, ... share the swizzle
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const int ch = 4 * db + 2 * (g4 & 1) + ((i16 & 3) >> 1);
+      v_off[db] = r * ROWB + ((ch ^ v_swizzle<D>(r)) * 16) + 8 * (i16 & 1);
+    }
+  }
+
+  // This workgroup's home queue is the one of the XCD it runs on (hardware register XCC_ID).
+  const int my_q = (int)(__builtin_amdgcn_s_getreg(kHwRegXccId) & 15u) % kXcds;
+  uint32_t* const q_head = p.queues;
+  const uint32_t* const q_end = p.queues + kXcds;
+
   for (;;) {
-    if (tid == 0) *s_item = (int)atomicAdd(p.counter, 1u);
+    if (tid == 0) {
+      // next item of the home queue; when that is drained, steal from the other XCDs' queues
+      int item = -1;
+      for (int k = 0; k < kXcds && item < 0; ++k) {
+        const int q = (my_q + k) % kXcds;
+        const uint32_t end = q_end[q];
+        if (__hip_atomic_load(q_head + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= end) continue;
+        const uint32_t got = atomicAdd(q_head + q, 1u);
+        if (got < end) item = (int)got;
+      }
+      s_item[0] = item;
+    }
     __syncthreads();
-    const int n = __builtin_amdgcn_readfirstlane(*s_item);
-    if (n >= p.N) break;
+    const int n = __builtin_amdgcn_readfirstlane(s_item[0]);
+    if (n < 0) break;
     const uint32_t entry = p.order[n];
     const int row = (int)(entry & ~kCopyFlag);
     const int bh = row / p.Tq;
@@ -222,12 +309,18 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     const char* Vh = p.V + head_off;
     const uint32_t* wp = p.words + (size_t)row * p.nw32;
 
-    // Q fragment: B operand of S^T = K Q^T; lane holds query row l32, d = 16*ks + 8*half .. +7
+    // Q fragment: B operand of S^T = K Q^T; lane holds query row l32, d = 16*ks + 8*half .. +7.
+    // It is multiplied by log2(e)/sqrt(D) once here (rounded back to bf16), so the MFMA result is
+    // already the exponent of 2 and the softmax needs no multiply per score.
     bf16x8 qf[KS];
     {
       const char* qrow = p.Q + blk_off + (size_t)(wave * 32 + l32) * ROWB + half * 16;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qrow + ks * 32);
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 q = *(const bf16x8*)(qrow + ks * 32);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[ks][e] = (__bf16)((float)q[e] * c);
+      }
     }
 
     f32x16 o[DB];
@@ -235,12 +328,21 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
-    float m_run = -INFINITY;
+    // Reference of the exponent (log2 domain) of this lane's query row, kept NEGATED in all 16
+    // registers of an accumulator: it is the C operand of the first MFMA of every S^T block, so
+    // the MFMA delivers score - reference and the softmax needs no subtraction per score either.
+    // The reference is not the running maximum: it is raised only when a score exceeds it by
+    // more than kRescaleLog2 (weights stay below 2^kRescaleLog2); the final division by the
+    // row sum cancels it exactly.
+    f32x16 neg_ref;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) neg_ref[e] = 0.f;
+    bool first = true;
     float l_run = 0.f;   // per-lane partial row sum (this lane's half of the keys)
 
     // scalar walk over the set bits of the decoded symbol row
     int w_idx = 0;
-    uint32_t w_bits = p.nw32 > 0 ? wp[0] : 0u;
+    uint32_t w_bits = wp[0];
     auto next_block = [&]() -> int {
       while (w_bits == 0u) {
         ++w_idx;
@@ -257,37 +359,44 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       const char* gK = Kh + tile_off;
       const char* gV = Vh + tile_off;
 #pragma unroll
-      for (int t = 0; t < NINST / NWAVES; ++t) {
-        const int inst = wave + t * NWAVES;
-        const int r = inst * ROWS_PER_INST + lane / CH;
-        const int pch = lane % CH;
-        const int ck = pch ^ k_swizzle<D>(r);
-        const int cv = pch ^ v_swizzle<D>(r);
-        __builtin_amdgcn_global_load_lds((GLOBAL_PTR(const void))(gK + r * ROWB + ck * 16),
-                                         (LDS_PTR(void))(ldsK + buf * TILEB + inst * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((GLOBAL_PTR(const void))(gV + r * ROWB + cv * 16),
-                                         (LDS_PTR(void))(ldsV + buf * TILEB + inst * 1024), 16, 0, 0);
+      for (int t = 0; t < NLOAD; ++t) {
+        const unsigned dst = (unsigned)(buf * TILEB + (wave + t * NWAVES) * 1024);
+        load_to_lds_16B(gK, k_goff[t], lds_base + dst);
+        load_to_lds_16B(gV, v_goff[t], lds_base + 2 * TILEB + dst);
       }
     };
 
     auto compute = [&](int buf) {
       const char* kb = ldsK + buf * TILEB;
       const char* vb = ldsV + buf * TILEB;
-      // S^T[key][query] for 64 keys: two 32x32 blocks
+      auto k_read = [&](int t) -> bf16x8 {   // operand t = (kb2, ks)
+        return *(const bf16x8*)(kb + (t / KS) * 32 * ROWB + k_off[t % KS]);
+      };
+      auto v_read = [&](int t) -> bf16x8 {   // operand t = ((kb2, ksp), db): keys 16*(t/DB) .. +15, d-block t%DB
+        const char* base = vb + (t / DB) * 16 * ROWB + v_off[t % DB];
+        const s16x4 t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(base));
+        const s16x4 t2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(base + 8 * ROWB));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(t1, t2, 0, 1, 2, 3, 4, 5, 6, 7));
+      };
+
+      // S^T[key][query] - reference, for 64 keys: two 32x32 blocks
       f32x16 s[2];
+      bf16x8 ka[NQK];
 #pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2) {
+      for (int t = 0; t < kPre; ++t) ka[t] = k_read(t);
+      __builtin_amdgcn_s_setprio(kMfmaPrio);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) s[kb2][e] = 0.f;
-        const int r = 32 * kb2 + l32;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const int ch = (2 * ks + half) ^ k_swizzle<D>(r);
-          const bf16x8 a = *(const bf16x8*)(kb + r * ROWB + ch * 16);
-          s[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb2], 0, 0, 0);
-        }
+      for (int t = 0; t < NQK; ++t) {
+        if (t + kPre < NQK) ka[t + kPre] = k_read(t + kPre);
+        s[t / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t], qf[t % KS], t % KS == 0 ? neg_ref : s[t / KS], 0, 0, 0);
       }
-      // online softmax; this lane sees 32 of the 64 scores of its query row
+      __builtin_amdgcn_s_setprio(0);
+      // first operands of the O^T product: fetched now, consumed after the softmax
+      bf16x8 va[NPV];
+#pragma unroll
+      for (int t = 0; t < kPre; ++t) va[t] = v_read(t);
+
+      // this lane sees 32 of the 64 scores of its query row; the other half sits in lane ^ 32
       float mx = s[0][0];
 #pragma unroll
       for (int kb2 = 0; kb2 < 2; ++kb2)
@@ -298,48 +407,52 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
         const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
         mx = fmaxf(__builtin_bit_cast(float, (unsigned)sw[0]), __builtin_bit_cast(float, (unsigned)sw[1]));
       }
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-      const float mc = m_new * c;
-      m_run = m_new;
-      float psum = 0.f;
+      if (first || __builtin_amdgcn_ballot_w64(mx > kRescaleLog2) != 0) {
+        // move the reference: to the row maximum on the first sub-tile, upwards only afterwards
+        const float d = first ? mx : fmaxf(mx, 0.f);
 #pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2)
+        for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][e], c, -mc));
-          s[kb2][e] = pv;
-          psum += pv;
+          for (int e = 0; e < 16; ++e) s[kb2][e] -= d;
+        if (!first) {
+          const float alpha = __builtin_amdgcn_exp2f(-d);
+          l_run *= alpha;
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
         }
-      l_run = l_run * alpha + psum;
+        const float nr = neg_ref[0] - d;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
-      // O^T += V^T P^T.  k-slot s of lane-half h maps to key 32*kb2 + 16*ksp + 8*(s/4) + 4*h + s%4,
+        for (int e = 0; e < 16; ++e) neg_ref[e] = nr;
+        first = false;
+      }
+      // weights, rounded to bf16 for the O^T product; the row sum adds up the same rounded values.
+      // k-slot s of lane-half h of the O^T MFMA maps to key 32*kb2 + 16*ksp + 8*(s/4) + 4*h + s%4,
       // which is exactly the key order of the S^T accumulator registers 8*ksp .. 8*ksp+7.
+      bf16x8 pb[4];
+      bf16x2 ones;
+      ones[0] = (__bf16)1.0f;
+      ones[1] = (__bf16)1.0f;
 #pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2) {
+      for (int g = 0; g < 4; ++g) {
 #pragma unroll
-        for (int ksp = 0; ksp < 2; ++ksp) {
-          bf16x8 pb;
+        for (int e = 0; e < 8; ++e) pb[g][e] = (__bf16)__builtin_amdgcn_exp2f(s[g >> 1][8 * (g & 1) + e]);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) pb[e] = (__bf16)s[kb2][8 * ksp + e];
-          const int r1 = 32 * kb2 + 16 * ksp + 4 * (g4 >> 1) + (i16 >> 2);
-          const int r2 = r1 + 8;
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            const int ch = 4 * db + 2 * (g4 & 1) + ((i16 & 3) >> 1);
-            const int within = 8 * (i16 & 1);
-            const s16x4 t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (LDS_PTR(s16x4))(vb + r1 * ROWB + ((ch ^ v_swizzle<D>(r1)) * 16) + within));
-            const s16x4 t2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (LDS_PTR(s16x4))(vb + r2 * ROWB + ((ch ^ v_swizzle<D>(r2)) * 16) + within));
-            const s16x8 a16 = __builtin_shufflevector(t1, t2, 0, 1, 2, 3, 4, 5, 6, 7);
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a16), pb, o[db], 0, 0, 0);
-          }
+        for (int e = 0; e < 8; e += 2) {
+          bf16x2 pr;
+          pr[0] = pb[g][e];
+          pr[1] = pb[g][e + 1];
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_run, false);
         }
       }
+      __builtin_amdgcn_s_setprio(kMfmaPrio);
+#pragma unroll
+      for (int t = 0; t < NPV; ++t) {
+        if (t + kPre < NPV) va[t + kPre] = v_read(t + kPre);
+        o[t % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[t], pb[t / DB], o[t % DB], 0, 0, 0);
+      }
+      __builtin_amdgcn_s_setprio(0);
     };
 
     int j = next_block();
@@ -386,6 +499,13 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     }
     __syncthreads();
   }
+#ifdef SA_DEBUG_CLOCKS
+  if (threadIdx.x == 0 && blockIdx.x < 1024) {
+    g_dbg_clocks[3 * blockIdx.x] = clock64() - dbg_c0;
+    g_dbg_clocks[3 * blockIdx.x + 1] = wall_clock64() - dbg_w0;
+    g_dbg_clocks[3 * blockIdx.x + 2] = __builtin_amdgcn_s_getreg(kHwRegXccId) & 15u;
+  }
+#endif
 }
 
 // ---------------------------------------------------------------------------------------
@@ -432,7 +552,7 @@ int check_shape(int B, int H, int L, int D, int bq, int bk, bool need_d, Shape* 
   return 0;
 }
 
-// scratch layout: [counter (256 B)] [order N u32] [keys N i32] [words N*nw32 u32]
+// scratch layout: [queue heads and ends (256 B)] [order N u32] [keys N i32] [words N*nw32 u32]
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 size_t workspace_bytes(const Shape& s) {
   return 256 + align256((size_t)s.N * 4) * 2 + align256((size_t)s.N * s.nw32 * 4);
@@ -511,7 +631,7 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
   void* ws = nullptr;
   if (int rc = get_scratch(workspace_bytes(s), stream, &ws)) return rc;
   char* base = (char*)ws;
-  uint32_t* counter = (uint32_t*)base;
+  uint32_t* queues = (uint32_t*)base;
   uint32_t* order = (uint32_t*)(base + 256);
   int32_t* keys = (int32_t*)(base + 256 + align256((size_t)s.N * 4));
   uint32_t* words = (uint32_t*)(base + 256 + 2 * align256((size_t)s.N * 4));
@@ -535,14 +655,15 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
   if (record) HIP_TRY(hipEventRecord(ev[0], stream));
 
   const int BH = B * H;
+  const int heads_per_xcd = (BH + kXcds - 1) / kXcds;
   int shift = 0;
-  while (((BH - 1) >> shift) + 1 > kMaxHeadGroups) ++shift;
-  const int groups = ((BH - 1) >> shift) + 1;
+  while (((heads_per_xcd - 1) >> shift) + 1 > kMaxHeadGroups) ++shift;
+  const int groups = ((heads_per_xcd - 1) >> shift) + 1;
   hipLaunchKernelGGL(plan_rows, dim3((s.N + 255) / 256), dim3(256), 0, stream, cache_flags, kv_mask, s.N, s.Tkv,
                      s.row_bytes, s.nw32, words, keys);
   HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(plan_order, dim3(1), dim3(kOrderThreads), 0, stream, keys, s.N, s.Tq, s.Tkv, shift, groups,
-                     order, counter);
+                     order, queues);
   HIP_TRY(hipGetLastError());
   if (record) HIP_TRY(hipEventRecord(ev[1], stream));
 
@@ -554,9 +675,10 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
   p.O = (char*)O;
   p.words = words;
   p.order = order;
-  p.counter = counter;
+  p.queues = queues;
   p.N = s.N;
   p.Tq = s.Tq;
+  p.Tkv = s.Tkv;
   p.L = L;
   p.nw32 = s.nw32;
   p.do_copy = (O_cache != nullptr && O_cache != O) ? 1 : 0;
@@ -703,6 +825,12 @@ int sparse_attn_profile_end(int* calls, double* plan_ms_total, double* attn_ms_t
   g_prof = Profile();
   return rc;
 }
+
+#ifdef SA_DEBUG_CLOCKS
+int sparse_attn_debug_clocks(unsigned long long* out, int n) {
+  return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg_clocks), sizeof(unsigned long long) * 3 * n) == hipSuccess ? 0 : -3;
+}
+#endif
 
 const char* sparse_attn_last_error(void) { return g_err; }
 
