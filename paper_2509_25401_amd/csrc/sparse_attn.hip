@@ -24,6 +24,7 @@
 
 #include <map>
 #include <mutex>
+#include <type_traits>
 #include <utility>
 
 #include "sparse_attn.h"
@@ -354,7 +355,8 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       return 32 * w_idx + b;
     };
 
-    auto issue_loads = [&](int j, int sub, int buf) {
+    auto issue_loads = [&](int j, int sub, auto buf_c) {
+      constexpr int buf = decltype(buf_c)::value;
       const size_t tile_off = ((size_t)j * BK + (size_t)sub * kKeys) * ROWB;
       const char* gK = Kh + tile_off;
       const char* gV = Vh + tile_off;
@@ -366,7 +368,10 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       }
     };
 
-    auto compute = [&](int buf) {
+    auto compute = [&](auto buf_c) {
+      // the buffer index is a compile-time constant, so every LDS address below is a per-lane
+      // register that never changes plus an immediate offset
+      constexpr int buf = decltype(buf_c)::value;
       const char* kb = ldsK + buf * TILEB;
       const char* vb = ldsV + buf * TILEB;
       auto k_read = [&](int t) -> bf16x8 {   // operand t = (kb2, ks)
@@ -455,23 +460,30 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       __builtin_amdgcn_s_setprio(0);
     };
 
+    // Two sub-tiles per trip, one per LDS buffer: while sub-tile u is computed from one buffer
+    // the loads of sub-tile u+1 are in flight into the other.
+    using Buf0 = std::integral_constant<int, 0>;
+    using Buf1 = std::integral_constant<int, 1>;
     int j = next_block();
     int sub = 0;
-    int buf = 0;
-    if (j >= 0) issue_loads(j, 0, 0);
-    while (j >= 0) {
+    if (j >= 0) issue_loads(j, 0, Buf0{});
+    auto step = [&](auto cur, auto other) {
       int nj = j, nsub = sub + 1;
       if (nsub == SUB) {
         nsub = 0;
         nj = next_block();
       }
       wait_vmem();
-      __syncthreads();   // sub-tile `buf` has landed for every wave; the other buffer is free
-      if (nj >= 0) issue_loads(nj, nsub, buf ^ 1);
-      compute(buf);
+      __syncthreads();   // this sub-tile has landed for every wave; the other buffer is free
+      if (nj >= 0) issue_loads(nj, nsub, other);
+      compute(cur);
       j = nj;
       sub = nsub;
-      buf ^= 1;
+    };
+    while (j >= 0) {
+      step(Buf0{}, Buf1{});
+      if (j < 0) break;
+      step(Buf1{}, Buf0{});
     }
 
     // O_i = diag(l)^-1 O_acc; both lane halves hold partial sums of the same row
