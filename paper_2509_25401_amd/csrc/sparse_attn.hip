@@ -4,17 +4,20 @@
 //   plan_rows   decodes the packed symbols of Section 3.3 once per (b,h,i) row into aligned
 //               32-bit words (bit j of the row = key block j, padding cleared) and counts the
 //               kept key blocks of every non-cached row;
-//   plan_order  orders the rows into a work list: heaviest rows first (16 count buckets), rows
-//               of one head adjacent inside a bucket so that concurrently running workgroups
-//               share that head's K/V in L2, cached rows (plain copies) last;
-//   attn        a persistent grid of workgroups pulls items from the list.  A compute item is
-//               one query block: Q lives in registers, the reduction-axis symbol is walked
-//               with scalar bit operations (find-first-set on the decoded words, no vector
-//               work), and only kept K/V tiles are streamed HBM -> LDS with direct-to-LDS
-//               loads, double buffered in 64-key sub-tiles.  S^T = K Q^T and O^T = V^T P^T run
-//               on v_mfma_f32_32x32x16_bf16, so each lane owns one query row: the row maximum
-//               needs a single half-wave exchange and the row sum none until the end.  A copy
-//               item moves one cached block O_cache -> O with 16-byte coalesced accesses.
+//   plan_order  sorts the rows into one work queue per XCD (a head's rows all go to one XCD, so
+//               its K/V stream through one L2): heaviest rows first (16 kept-count buckets), rows
+//               of one head adjacent inside a bucket, cached rows (plain copies) last;
+//   attn        a persistent grid of two workgroups per CU pulls items from its XCD's queue and
+//               steals from the others when that is drained.  A compute item is one query block:
+//               Q lives in registers (pre-multiplied by log2(e)/sqrt(D)), the reduction-axis
+//               symbol is walked with scalar find-first-set on the decoded words, and only kept
+//               K/V tiles are streamed to LDS with direct-to-LDS loads, double buffered in 64-key
+//               sub-tiles.  S^T = K Q^T and O^T = V^T P^T run on v_mfma_f32_32x32x16_bf16, so
+//               each lane owns one query row: the row maximum needs a single half-wave exchange,
+//               the row sum none until the end, and the exponentiated S^T accumulators are the
+//               B operand of the O^T product without any data movement.  The reference of the
+//               exponent is the C operand of the first S^T MFMA and moves only when a score
+//               exceeds it by 2^8.  A copy item moves one cached block O_cache -> O.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdarg.h>
@@ -50,14 +53,8 @@ constexpr int kMaxTq = 16384;
 constexpr unsigned kCopyFlag = 0x80000000u;
 constexpr int kHwRegXccId = (3 << 11) | 20;   // s_getreg operand: 4 bits at offset 0 of hardware register 20 (XCC_ID)
 constexpr int kOrderThreads = 1024;
-#ifndef SA_RESCALE_LOG2
-#define SA_RESCALE_LOG2 8.0f
-#endif
-#ifndef SA_MFMA_PRIO
-#define SA_MFMA_PRIO 1
-#endif
-constexpr int kMfmaPrio = SA_MFMA_PRIO;            // wave priority while it feeds the matrix pipe
-constexpr float kRescaleLog2 = SA_RESCALE_LOG2;   // how far a score may exceed the exponent's reference
+constexpr int kMfmaPrio = 1;            // wave priority while it feeds the matrix pipe
+constexpr float kRescaleLog2 = 8.0f;    // how far (log2) a score may exceed the exponent's reference before it moves
 
 struct AttnParams {
   const char* Q;
@@ -202,15 +199,9 @@ __device__ __forceinline__ void wait_vmem() {
   __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
-#ifdef SA_DEBUG_CLOCKS
-__device__ unsigned long long g_dbg_clocks[3 * 1024];
-#endif
 
 template <int D, int BQ, int BK>
 __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
-#ifdef SA_DEBUG_CLOCKS
-  const unsigned long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
-#endif
   constexpr int NWAVES = BQ / 32;
   constexpr int NT = NWAVES * 64;
   constexpr int SUB = BK / kKeys;          // LDS sub-tiles per symbol bit
@@ -511,13 +502,6 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     }
     __syncthreads();
   }
-#ifdef SA_DEBUG_CLOCKS
-  if (threadIdx.x == 0 && blockIdx.x < 1024) {
-    g_dbg_clocks[3 * blockIdx.x] = clock64() - dbg_c0;
-    g_dbg_clocks[3 * blockIdx.x + 1] = wall_clock64() - dbg_w0;
-    g_dbg_clocks[3 * blockIdx.x + 2] = __builtin_amdgcn_s_getreg(kHwRegXccId) & 15u;
-  }
-#endif
 }
 
 // ---------------------------------------------------------------------------------------
@@ -695,6 +679,7 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
   p.nw32 = s.nw32;
   p.do_copy = (O_cache != nullptr && O_cache != O) ? 1 : 0;
   p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
+  // persistent grid: two workgroups per CU (64 KiB of LDS each), fewer if there are fewer items
   const int grid = s.N < 2 * cus ? s.N : 2 * cus;
 
   int rc = 0;
@@ -838,11 +823,6 @@ int sparse_attn_profile_end(int* calls, double* plan_ms_total, double* attn_ms_t
   return rc;
 }
 
-#ifdef SA_DEBUG_CLOCKS
-int sparse_attn_debug_clocks(unsigned long long* out, int n) {
-  return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg_clocks), sizeof(unsigned long long) * 3 * n) == hipSuccess ? 0 : -3;
-}
-#endif
 
 const char* sparse_attn_last_error(void) { return g_err; }
 
