@@ -26,7 +26,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
-HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the attention kernel on the headline workload, from the rocprofv3 --pmc
+# passes summarised in profiles/attn_kernel_video33k_keep25_counters.txt (FETCH_SIZE and WRITE_SIZE,
+# each scaled by the same counter's reading for a plain 1 GiB copy).  Only valid for that workload.
+MEASURED_TRAFFIC_BYTES = {"keep=0.25 heads=24": 16.9e6 * 1024 + 198677 * 1024}
 
 
 def log(msg):
@@ -146,6 +149,7 @@ def main():
     extra["sparsity"] = 1.0 - head["keep"]
     extra["plan_ms"] = head["plan_ms"]
     extra["attn_kernel_ms"] = head["attn_ms"]
+    extra["algorithmic_hbm_bytes"] = 4 * w.B * w.H * w.L * w.D * 2
     extra["paper_context"] = "A100 BF16: ~4.6x at 80% block-sparse skipping, ~9.4x at 90% combined sparsity (other hardware)"
 
     cpu = None
@@ -186,7 +190,8 @@ def main():
                                f"band+text+random mask at {head['keep'] * 100:.1f}% keep, no cached blocks",
                    "kept_pairs": head["kept_pairs"], "total_pairs": total_pairs},
         "roofline": {"bound": "mfma", "achieved": head["kernel_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": head["kernel_tflops"] / PEAK_BF16_TFLOPS, "traffic": None},
+                     "frac": head["kernel_tflops"] / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(f"keep={args.keep:g} heads={H}")},
         "cpu_baseline": cpu,
         "extra": extra,
     }
