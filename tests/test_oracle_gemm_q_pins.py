@@ -1,0 +1,83 @@
+"""Pins of the GEMM-Q oracle (sparse query projection, Section 3.5): things the mathematics fixes
+independently of the oracle's own matmul call."""
+import numpy as np
+
+import oracle
+from paper_2509_25401_amd import synth
+from helpers import bits_to_f64
+
+
+def _case(seed, B, L, C, H, D, bq, cached=0.3, bias=True):
+    r = np.random.default_rng(seed)
+    X = synth.normal_bf16(r, (B, L, C))
+    W = synth.f32_to_bf16_bits((r.standard_normal((H * D, C)) / np.sqrt(C)).astype(np.float32))
+    b = synth.normal_bf16(r, (H * D,)) if bias else None
+    flags = (r.random((B, H, L // bq)) < cached).astype(np.uint8) if cached > 0 else None
+    return X, W, b, flags
+
+
+def test_brute_force_loops_on_tiny_shapes():
+    B, L, C, H, D, bq = 2, 8, 5, 3, 2, 4
+    X, W, b, flags = _case(1, B, L, C, H, D, bq, cached=0.4)
+    Q, _ = oracle.gemm_q(X, W, b, flags, bq, H, D)
+    Xf, Wf, bf = bits_to_f64(X), bits_to_f64(W), bits_to_f64(b)
+    for bb in range(B):
+        for h in range(H):
+            for l in range(L):
+                for d in range(D):
+                    if flags[bb, h, l // bq]:
+                        assert Q[bb, h, l, d] == 0.0
+                        continue
+                    acc = 0.0
+                    for c in range(C):
+                        acc += Xf[bb, l, c] * Wf[h * D + d, c]
+                    assert abs(Q[bb, h, l, d] - (acc + bf[h * D + d])) < 1e-12
+
+
+def test_one_hot_inputs_select_weight_entries():
+    """X[l] = e_{l mod C} makes Q[b,h,l,d] = W[h*D+d, l mod C]: pins the operand orientation and the head split."""
+    B, L, C, H, D, bq = 1, 64, 16, 2, 8, 32
+    r = np.random.default_rng(2)
+    W = synth.normal_bf16(r, (H * D, C))
+    Xf = np.zeros((B, L, C), dtype=np.float32)
+    Xf[0, np.arange(L), np.arange(L) % C] = 1.0
+    Q, Qb = oracle.gemm_q(synth.f32_to_bf16_bits(Xf), W, None, None, bq, H, D)
+    Wf = bits_to_f64(W)
+    for h in range(H):
+        for l in range(L):
+            assert (Q[0, h, l] == Wf[h * D:(h + 1) * D, l % C]).all()
+    assert (Qb == W.reshape(H, D, C).transpose(0, 2, 1)[None, :, np.arange(L) % C, :]).all()
+
+
+def test_identity_weight_reshapes_x_into_heads():
+    B, L, H, D, bq = 2, 32, 3, 4, 16
+    C = H * D
+    r = np.random.default_rng(3)
+    X = synth.normal_bf16(r, (B, L, C))
+    W = synth.f32_to_bf16_bits(np.eye(C, dtype=np.float32))
+    _, Qb = oracle.gemm_q(X, W, None, None, bq, H, D)
+    assert (Qb == X.reshape(B, L, H, D).transpose(0, 2, 1, 3)).all()
+
+
+def test_flagged_blocks_are_left_untouched_and_the_rest_ignores_them():
+    B, L, C, H, D, bq = 1, 64, 32, 4, 8, 16
+    X, W, b, flags = _case(4, B, L, C, H, D, bq, cached=0.5)
+    init = np.full((B, H, L, D), 0x4242, dtype=np.uint16)
+    Q, Qb = oracle.gemm_q(X, W, b, flags, bq, H, D, Q_init_bits=init)
+    Qd, Qdb = oracle.gemm_q(X, W, b, None, bq, H, D)
+    skipped = np.repeat(flags != 0, bq, axis=2)
+    assert skipped.any() and (~skipped).any()
+    assert (Qb[skipped] == 0x4242).all()
+    assert (Qb[~skipped] == Qdb[~skipped]).all() and (Q[~skipped] == Qd[~skipped]).all()
+    assert oracle.gemm_q_flops(flags, B, H, L, C, D, bq) == 2.0 * bq * D * C * int((flags == 0).sum())
+
+
+def test_linearity_and_bias():
+    B, L, C, H, D, bq = 1, 32, 16, 2, 8, 16
+    X, W, b, _ = _case(5, B, L, C, H, D, bq, cached=0)
+    Q1, _ = oracle.gemm_q(X, W, None, None, bq, H, D)
+    Q2, _ = oracle.gemm_q(X, W, b, None, bq, H, D)
+    assert np.abs((Q2 - Q1) - bits_to_f64(b).reshape(H, 1, D)[None]).max() < 1e-12
+    X2 = synth.f32_to_bf16_bits(2.0 * synth.bf16_bits_to_f32(X))      # exact in bf16
+    Q3, _ = oracle.gemm_q(X2, W, None, None, bq, H, D)
+    assert np.abs(Q3 - 2.0 * Q1).max() < 1e-12
