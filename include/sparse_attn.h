@@ -90,6 +90,27 @@ int sparse_attn_fwd_timed(const void* Q, const void* K, const void* V,
                           void* hip_stream, float* plan_ms, float* attn_ms);
 
 /*
+ * Sparse query projection (GEMM-Q, Section 3.5, Observation 2 / Equation 2): the step right before
+ * the attention call.  For every (b, h, i) whose cache flag is clear
+ *     Q[b, h, i*block_q : (i+1)*block_q, :] = X[b, i*block_q : (i+1)*block_q, :] . W_h^T (+ bias_h)
+ * and a flagged block of Q is left untouched (its attention output is reused from the cache, so its
+ * queries are never read).  The per-token RMSNorm and RoPE of Equation 2 are not part of this call.
+ *   X            device, bf16 [B, L, C], C fastest
+ *   W            device, bf16 [H*D, C]: one row per output feature (the layout a Linear layer
+ *                stores), head h owns rows h*D .. (h+1)*D-1
+ *   bias         device, bf16 [H*D], or NULL
+ *   cache_flags  device, uint8 [B, H, L/block_q], same meaning as in sparse_attn_fwd, or NULL
+ *   Q            device, bf16 [B, H, L, D], written for the computed blocks (fp32 accumulation,
+ *                rounded to nearest even); must not overlap X or W
+ * Supported: D and block_q in {64, 128}, C a multiple of 64, L a multiple of block_q.
+ * Errors as for sparse_attn_fwd.  Allocates nothing.
+ */
+int sparse_gemm_q(const void* X, const void* W, const void* bias, const uint8_t* cache_flags, void* Q,
+                  int B, int L, int C, int H, int D, int block_q);
+int sparse_gemm_q_stream(const void* X, const void* W, const void* bias, const uint8_t* cache_flags, void* Q,
+                         int B, int L, int C, int H, int D, int block_q, void* hip_stream);
+
+/*
  * Live kernel timing for benchmarks.  Between sparse_attn_profile_begin(max_calls) and
  * sparse_attn_profile_end(), each of the first max_calls calls of sparse_attn_fwd /
  * sparse_attn_fwd_stream records three HIP events on its own stream (start, after the symbol

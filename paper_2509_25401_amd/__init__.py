@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     load_library,
     sparse_attn_fwd,
     sparse_attn_fwd_timed,
+    sparse_gemm_q,
     sparse_attn_profile_begin,
     sparse_attn_profile_end,
     sparse_attn_pack_mask,

@@ -48,6 +48,10 @@ def load_library():
     lib.sparse_attn_count_kept.restype = i32
     lib.sparse_attn_pack_mask.argtypes = [vp, ctypes.c_longlong, i32, vp]
     lib.sparse_attn_pack_mask.restype = i32
+    lib.sparse_gemm_q.argtypes = [vp] * 5 + [i32] * 6
+    lib.sparse_gemm_q.restype = i32
+    lib.sparse_gemm_q_stream.argtypes = [vp] * 5 + [i32] * 6 + [vp]
+    lib.sparse_gemm_q_stream.restype = i32
     lib.sparse_attn_profile_begin.argtypes = [i32]
     lib.sparse_attn_profile_begin.restype = i32
     lib.sparse_attn_profile_end.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -122,6 +126,21 @@ def sparse_attn_fwd_timed(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, bl
     if rc != 0:
         _raise(rc)
     return plan.value, attn.value
+
+
+def sparse_gemm_q(X, W, bias, cache_flags, Q, block_q, stream=None):
+    """Sparse query projection on device tensors: X bf16 [B,L,C], W bf16 [H*D,C], bias bf16 [H*D] or None,
+    cache_flags uint8 [B,H,L/block_q] or None, Q bf16 [B,H,L,D] written in place for the computed blocks."""
+    B, L, C = X.shape
+    _, H, _, D = Q.shape
+    if tuple(W.shape) != (H * D, C) or Q.shape[0] != B or Q.shape[2] != L:
+        raise ValueError("shapes of X [B,L,C], W [H*D,C] and Q [B,H,L,D] do not fit together")
+    rc = load_library().sparse_gemm_q_stream(_dev_ptr(X, "X"), _dev_ptr(W, "W"), _dev_ptr(bias, "bias", True),
+                                             _dev_ptr(cache_flags, "cache_flags", True), _dev_ptr(Q, "Q"),
+                                             int(B), int(L), int(C), int(H), int(D), int(block_q), _stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
+    return Q
 
 
 def sparse_attn_profile_begin(max_calls: int) -> None:

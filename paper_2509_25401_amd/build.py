@@ -1,11 +1,11 @@
-"""Compile csrc/sparse_attn.hip into libsparse_attn_hip.so for gfx950 (in-tree, plain hipcc)."""
+"""Compile csrc/*.hip into libsparse_attn_hip.so for gfx950 (in-tree, plain hipcc)."""
 import os
 import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "sparse_attn.hip")
+SRCS = [os.path.join(HERE, "csrc", n) for n in ("sparse_attn.hip", "sparse_gemm_q.hip")]
 LIB = os.path.join(HERE, "libsparse_attn_hip.so")
 
 
@@ -21,7 +21,7 @@ def build(verbose: bool = False, extra=()) -> str:
            "-I", os.path.join(ROOT, "include"),
            # packed fp32 VALU forms are kept out of the generated code on purpose
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-o", LIB, SRC, *extra]
+           "-o", LIB, *SRCS, *extra]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

@@ -31,6 +31,7 @@
 #include <utility>
 
 #include "sparse_attn.h"
+#include "sparse_attn_internal.h"
 
 namespace {
 
@@ -509,13 +510,19 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
 // ---------------------------------------------------------------------------------------
 thread_local char g_err[512] = "";
 
-int fail(int code, const char* fmt, ...) {
+}  // namespace
+
+int sa_fail(int code, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
   vsnprintf(g_err, sizeof g_err, fmt, ap);
   va_end(ap);
   return code;
 }
+
+namespace {
+
+#define fail sa_fail
 
 #define HIP_TRY(expr)                                                                          \
   do {                                                                                         \

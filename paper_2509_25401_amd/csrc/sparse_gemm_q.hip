@@ -1,0 +1,259 @@
+// Sparse query projection (GEMM-Q of the paper, Section 3.5, Observation 2 / Equation 2) for gfx950.
+//
+// Q[b,h,i-th block,:] = X[b, i-th block, :] . W_h^T (+ bias_h) for every (b,h,i) whose cache flag
+// is clear; a workgroup whose tile is flagged returns at once (its attention output is reused from
+// the cache, so its queries are never read).  One workgroup per (query block, head) output tile, the
+// same granularity as the flags, written straight into the [B,H,L,D] layout the attention kernel
+// reads.  The product is computed transposed, C^T[d][token] = sum_k W[d][k] X[token][k], with
+// v_mfma_f32_32x32x16_bf16: both operands are "k contiguous" rows (A = weight rows, B = token
+// rows), so both come out of LDS with plain 16-byte reads, and a lane ends up holding 4 consecutive
+// d of one token, which stores as 8 bytes.  X and W tiles stream to LDS with direct-to-LDS loads,
+// 64 channels per stage, double buffered.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "sparse_attn.h"
+#include "sparse_attn_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+#define LDS_PTR(T) T __attribute__((address_space(3)))*
+
+constexpr int kStepK = 64;                 // channels per LDS stage
+constexpr int kRowB = kStepK * 2;          // bytes per tile row in LDS
+
+struct GemmQParams {
+  const char* X;       // bf16 [B, L, C]
+  const char* W;       // bf16 [H*D, C]
+  const uint16_t* bias;  // bf16 [H*D] or nullptr
+  const uint8_t* flags;  // [B, H, Tq] or nullptr
+  char* Q;             // bf16 [B, H, L, D]
+  int H, L, C, Tq;
+};
+
+// 16-byte chunk permutation of a 128-byte tile row (two rows share a 256-byte bank line)
+__device__ __forceinline__ int row_swizzle(int row) { return (row >> 1) & 7; }
+
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void gq_load_to_lds_16B(const char* gbase, unsigned lane_off, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(lane_off), "s"(gbase)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+template <int BQ, int D>
+__global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(const GemmQParams p) {
+  constexpr int WM = BQ / 64;              // waves along tokens
+  constexpr int WN = D / 64;               // waves along head channels
+  constexpr int NWAVES = WM * WN;
+  constexpr int W_TILEB = D * kRowB;       // bytes of one weight stage
+  constexpr int X_TILEB = BQ * kRowB;      // bytes of one token stage
+  constexpr int W_INST = W_TILEB / 1024;   // direct-to-LDS wave instructions per weight stage
+  constexpr int X_INST = X_TILEB / 1024;
+  constexpr int W_LOAD = (W_INST + NWAVES - 1) / NWAVES;
+  constexpr int X_LOAD = (X_INST + NWAVES - 1) / NWAVES;
+  static_assert(W_INST % NWAVES == 0 && X_INST % NWAVES == 0, "stage loads must split evenly over the waves");
+
+  // tile of this workgroup: head fastest, so the 8 XCDs (workgroup n runs on XCD n mod 8) each keep
+  // the weights of a fixed set of heads in their L2
+  const int t = blockIdx.x;
+  const int h = t % p.H;
+  const int i = (t / p.H) % p.Tq;
+  const int b = t / (p.H * p.Tq);
+  if (p.flags && p.flags[((size_t)b * p.H + h) * p.Tq + i]) return;   // spatial-axis symbol says: cached
+
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  // layout: W stage 0, W stage 1, X stage 0, X stage 1
+  const unsigned lds_base = (unsigned)(uintptr_t)(LDS_PTR(char))smem;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WM, wn = wave / WM;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  const size_t row_pitch = (size_t)p.C * 2;
+  const char* gW = p.W + (size_t)h * D * row_pitch;
+  const char* gX = p.X + ((size_t)b * p.L + (size_t)i * BQ) * row_pitch;
+
+  // per-lane global offsets of this wave's stage loads (8 rows of 128 bytes per instruction)
+  unsigned w_goff[W_LOAD], x_goff[X_LOAD];
+#pragma unroll
+  for (int u = 0; u < W_LOAD; ++u) {
+    const int r = (wave + u * NWAVES) * 8 + lane / 8;
+    w_goff[u] = (unsigned)(r * row_pitch + (((lane % 8) ^ row_swizzle(r)) * 16));
+  }
+#pragma unroll
+  for (int u = 0; u < X_LOAD; ++u) {
+    const int r = (wave + u * NWAVES) * 8 + lane / 8;
+    x_goff[u] = (unsigned)(r * row_pitch + (((lane % 8) ^ row_swizzle(r)) * 16));
+  }
+  // per-lane LDS offsets of the operand reads: row l32 of a 32-row block, k-step ks
+  int op_off[kStepK / 16];
+#pragma unroll
+  for (int ks = 0; ks < kStepK / 16; ++ks) op_off[ks] = l32 * kRowB + (((2 * ks + half) ^ row_swizzle(l32)) * 16);
+
+  auto issue = [&](int kstep, auto stage_c) {
+    constexpr int stage = decltype(stage_c)::value;
+    const char* w_src = gW + (size_t)kstep * kRowB;
+    const char* x_src = gX + (size_t)kstep * kRowB;
+#pragma unroll
+    for (int u = 0; u < W_LOAD; ++u)
+      gq_load_to_lds_16B(w_src, w_goff[u], lds_base + (unsigned)(stage * W_TILEB + (wave + u * NWAVES) * 1024));
+#pragma unroll
+    for (int u = 0; u < X_LOAD; ++u)
+      gq_load_to_lds_16B(x_src, x_goff[u],
+                         lds_base + (unsigned)(2 * W_TILEB + stage * X_TILEB + (wave + u * NWAVES) * 1024));
+  };
+
+  f32x16 acc[2][2];   // [d block][token block] of this wave's 64x64 corner
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[a][c][e] = 0.f;
+
+  auto compute = [&](auto stage_c) {
+    constexpr int stage = decltype(stage_c)::value;
+    const char* wt = smem + stage * W_TILEB + (wn * 64) * kRowB;
+    const char* xt = smem + 2 * W_TILEB + stage * X_TILEB + (wm * 64) * kRowB;
+    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int ks = 0; ks < kStepK / 16; ++ks) {
+      bf16x8 wa[2], xb[2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) wa[a] = *(const bf16x8*)(wt + a * 32 * kRowB + op_off[ks]);
+#pragma unroll
+      for (int c = 0; c < 2; ++c) xb[c] = *(const bf16x8*)(xt + c * 32 * kRowB + op_off[ks]);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+          acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], xb[c], acc[a][c], 0, 0, 0);
+    }
+    __builtin_amdgcn_s_setprio(0);
+  };
+
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+  const int nk = p.C / kStepK;
+  issue(0, S0{});
+  for (int k = 0; k < nk; k += 2) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the stage has landed
+    __syncthreads();
+    if (k + 1 < nk) issue(k + 1, S1{});
+    compute(S0{});
+    if (k + 1 >= nk) break;
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (k + 2 < nk) issue(k + 2, S0{});
+    compute(S1{});
+  }
+
+  // epilogue: lane holds token l32 (+32*c) and, per accumulator quad q4, head channels
+  // 32*a + 8*q4 + 4*half + 0..3 of this wave's corner
+  char* qrow0 = p.Q + (((size_t)b * p.H + h) * p.L + (size_t)i * BQ + wm * 64 + l32) * (size_t)(D * 2);
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int d0 = wn * 64 + 32 * a + 8 * q4 + 4 * half;
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (p.bias) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          bv[e] = __builtin_bit_cast(float, (unsigned)p.bias[h * D + d0 + e] << 16);
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        bf16x2 lo, hi;
+        lo[0] = (__bf16)(acc[a][c][4 * q4 + 0] + bv[0]);
+        lo[1] = (__bf16)(acc[a][c][4 * q4 + 1] + bv[1]);
+        hi[0] = (__bf16)(acc[a][c][4 * q4 + 2] + bv[2]);
+        hi[1] = (__bf16)(acc[a][c][4 * q4 + 3] + bv[3]);
+        u32x2 pk;
+        pk[0] = __builtin_bit_cast(unsigned, lo);
+        pk[1] = __builtin_bit_cast(unsigned, hi);
+        *(u32x2*)(qrow0 + (size_t)c * 32 * (D * 2) + d0 * 2) = pk;
+      }
+    }
+}
+
+template <int BQ, int D>
+int launch(const GemmQParams& p, int tiles, hipStream_t stream) {
+  constexpr size_t lds = 2 * (size_t)(D + BQ) * kRowB;
+  constexpr int threads = (BQ / 64) * (D / 64) * 64;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_q_kernel<BQ, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    if (e != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_q_kernel<BQ, D>), dim3(tiles), dim3(threads), lds, stream, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "gemm_q launch failed: %s", hipGetErrorString(e));
+  return 0;
+}
+
+bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
+  const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + nb && y < x + na;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sparse_gemm_q_stream(const void* X, const void* W, const void* bias, const uint8_t* cache_flags, void* Q, int B,
+                         int L, int C, int H, int D, int block_q, void* hip_stream) {
+  if (B <= 0 || L <= 0 || C <= 0 || H <= 0 || D <= 0 || block_q <= 0)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: sizes must be positive (B=%d L=%d C=%d H=%d D=%d block_q=%d)", B,
+                   L, C, H, D, block_q);
+  if ((D != 64 && D != 128) || (block_q != 64 && block_q != 128))
+    return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_q: D and block_q must be 64 or 128 (got %d, %d)", D, block_q);
+  if (C % kStepK) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_q: C=%d must be a multiple of %d", C, kStepK);
+  if (L % block_q) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: L=%d must be a multiple of block_q=%d", L, block_q);
+  if ((long long)128 * C * 2 >= (1LL << 31)) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_q: C=%d too large", C);
+  const long long tiles = (long long)B * H * (L / block_q);
+  if (tiles > 0x3fffffffLL) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_q: too many tiles (%lld)", tiles);
+  if (!X || !W || !Q) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: X, W and Q must not be NULL");
+  if (((uintptr_t)X | (uintptr_t)W | (uintptr_t)Q) & 15)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: X, W and Q must be 16-byte aligned");
+  const size_t xb = (size_t)B * L * C * 2, wb = (size_t)H * D * C * 2, qb = (size_t)B * H * L * D * 2;
+  if (ranges_overlap(Q, qb, X, xb) || ranges_overlap(Q, qb, W, wb))
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: Q must not overlap X or W");
+
+  GemmQParams p;
+  p.X = (const char*)X;
+  p.W = (const char*)W;
+  p.bias = (const uint16_t*)bias;
+  p.flags = cache_flags;
+  p.Q = (char*)Q;
+  p.H = H;
+  p.L = L;
+  p.C = C;
+  p.Tq = L / block_q;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (block_q == 128 && D == 128) return launch<128, 128>(p, (int)tiles, stream);
+  if (block_q == 128 && D == 64) return launch<128, 64>(p, (int)tiles, stream);
+  if (block_q == 64 && D == 128) return launch<64, 128>(p, (int)tiles, stream);
+  return launch<64, 64>(p, (int)tiles, stream);
+}
+
+int sparse_gemm_q(const void* X, const void* W, const void* bias, const uint8_t* cache_flags, void* Q, int B, int L,
+                  int C, int H, int D, int block_q) {
+  return sparse_gemm_q_stream(X, W, bias, cache_flags, Q, B, L, C, H, D, block_q, nullptr);
+}
+
+}  // extern "C"

@@ -22,14 +22,14 @@ def _declared_functions():
             continue
         text = open(os.path.join(inc, fn)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names += re.findall(r"\b(sparse_attn_\w+)\s*\(", text)
+        names += re.findall(r"\b(sparse_(?:attn|gemm)_\w+)\s*\(", text)
     return sorted(set(names))
 
 
 def test_library_exports_every_declared_symbol():
     lib = pkg.load_library()
     names = _declared_functions()
-    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and len(names) >= 8
+    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and len(names) >= 10
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
     assert pkg.sparse_attn_version() >= 100
@@ -95,3 +95,21 @@ def test_workload_recipes_hit_their_keep_ratios():
     assert (w3.cache_flags.sum(axis=-1) == 18).all() and (w3.cache_flags[..., :4] == 0).all()
     rows = w3.M_s[w3.cache_flags == 0]
     assert abs(rows.mean() - 0.3) < 0.01
+
+
+def _gemm_q(B=1, L=128, C=64, H=1, D=128, bq=128, X=FAKE, W=ctypes.c_void_p(0x20000000), Q=ctypes.c_void_p(0x90000000)):
+    return pkg.load_library().sparse_gemm_q(X, W, None, None, Q, B, L, C, H, D, bq)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(B=0), -1), (dict(L=0), -1), (dict(C=0), -1), (dict(H=0), -1), (dict(D=0), -1), (dict(bq=0), -1),
+    (dict(L=192), -1),                   # not a multiple of block_q
+    (dict(C=96), -2),                    # channels must come in stages of 64
+    (dict(D=96), -2), (dict(bq=32), -2),
+    (dict(X=None), -1), (dict(W=None), -1), (dict(Q=None), -1),
+    (dict(Q=FAKE), -1),                  # Q aliases X
+    (dict(X=ctypes.c_void_p(0x10004)), -1),
+])
+def test_gemm_q_argument_validation_precedes_any_device_work(kw, code):
+    assert _gemm_q(**kw) == code
+    assert pkg.sparse_attn_last_error() != ""

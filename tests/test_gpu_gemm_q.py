@@ -1,0 +1,96 @@
+"""GPU parity of the sparse query projection (GEMM-Q) against its CPU oracle.
+
+Bar: skipped blocks bit-identical to what was in Q before the call; computed elements within one
+bf16 rounding of the fp64 result: |got - ref| <= 2^-8 |ref| + 1e-3 (fp32 accumulation of C <= 3072
+products of O(1) terms contributes < 1e-4)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_25401_amd as pkg
+from paper_2509_25401_amd import synth
+from gpu_utils import up_bf16, up_u8, down_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(seed, B, L, C, H, D, bq, cached, bias=True):
+    r = np.random.default_rng(seed)
+    X = synth.normal_bf16(r, (B, L, C))
+    W = synth.f32_to_bf16_bits((r.standard_normal((H * D, C)) / np.sqrt(C)).astype(np.float32))
+    b = synth.normal_bf16(r, (H * D,)) if bias else None
+    flags = (r.random((B, H, L // bq)) < cached).astype(np.uint8) if cached > 0 else None
+    return X, W, b, flags
+
+
+def _run(X, W, b, flags, B, L, C, H, D, bq, fill=0x4242):
+    Q = torch.from_numpy(np.full((B, H, L, D), fill, dtype=np.uint16).view(np.int16)).view(torch.bfloat16).to("cuda:0")
+    pkg.sparse_gemm_q(up_bf16(X), up_bf16(W), None if b is None else up_bf16(b), up_u8(flags), Q, bq)
+    torch.cuda.synchronize()
+    return down_bits(Q)
+
+
+def _check(got_bits, ref, ref_bits, flags, bq, label):
+    skipped = np.zeros(got_bits.shape[:3], dtype=bool) if flags is None else np.repeat(flags != 0, bq, axis=2)
+    if skipped.any():
+        assert (got_bits[skipped] == 0x4242).all(), f"{label}: skipped blocks were written"
+    got = synth.bf16_bits_to_f32(got_bits).astype(np.float64)[~skipped]
+    want = ref[~skipped]
+    err = np.abs(got - want)
+    tol = np.abs(want) * 2.0 ** -8 + 1e-3
+    exact = (got_bits[~skipped] == ref_bits[~skipped]).mean()
+    print(f"[parity] {label}: max-abs {err.max():.3e}, bit-identical to the rounded oracle: {exact * 100:.2f}%", flush=True)
+    assert (err <= tol).all(), f"{label}: max violation {(err - tol).max()}"
+    assert exact > 0.98
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("bq", [64, 128])
+def test_small_cases_all_variants(D, bq):
+    print(f"[case] gemm_q small D={D} bq={bq}", flush=True)
+    B, L, C, H = 2, 384, 320, 3       # C = 5 stages of 64: odd number of stages
+    X, W, b, flags = _case(10 + D + bq, B, L, C, H, D, bq, cached=0.3)
+    got = _run(X, W, b, flags, B, L, C, H, D, bq)
+    ref, ref_bits = oracle.gemm_q(X, W, b, flags, bq, H, D)
+    _check(got, ref, ref_bits, flags, bq, f"gemm_q D={D} bq={bq}")
+
+
+def test_single_stage_and_no_bias_no_flags():
+    print("[case] gemm_q C=64", flush=True)
+    B, L, C, H, D, bq = 1, 256, 64, 2, 128, 128
+    X, W, _, _ = _case(20, B, L, C, H, D, bq, cached=0, bias=False)
+    got = _run(X, W, None, None, B, L, C, H, D, bq)
+    ref, ref_bits = oracle.gemm_q(X, W, None, None, bq, H, D)
+    _check(got, ref, ref_bits, None, bq, "gemm_q C=64")
+
+
+def test_one_hot_tokens_select_weight_entries_exactly():
+    print("[case] gemm_q one-hot", flush=True)
+    B, L, C, H, D, bq = 1, 256, 128, 2, 64, 64
+    r = np.random.default_rng(21)
+    W = synth.normal_bf16(r, (H * D, C))
+    Xf = np.zeros((B, L, C), dtype=np.float32)
+    Xf[0, np.arange(L), (np.arange(L) * 7) % C] = 1.0
+    got = _run(synth.f32_to_bf16_bits(Xf), W, None, None, B, L, C, H, D, bq)
+    expect = W.reshape(H, D, C).transpose(0, 2, 1)[None, :, (np.arange(L) * 7) % C, :]
+    assert (got == expect).all()
+
+
+def test_all_blocks_flagged_writes_nothing():
+    B, L, C, H, D, bq = 1, 256, 128, 2, 128, 128
+    X, W, b, _ = _case(22, B, L, C, H, D, bq, cached=0)
+    got = _run(X, W, b, np.ones((B, H, L // bq), dtype=np.uint8), B, L, C, H, D, bq)
+    assert (got == 0x4242).all()
+
+
+def test_image_dit_shape_with_flags_feeds_attention():
+    """FLUX-like projection (4608 tokens, 3072 channels, 24 heads of 128) with config 3's flags; the
+    projected queries of the computed blocks then go through the attention kernel and its oracle."""
+    print("[case] gemm_q image-DiT shape", flush=True)
+    w = synth.config_image_cache_skip()
+    B, L, C, H, D, bq = 1, w.L, 3072, w.H, w.D, w.block_q
+    X, W, b, _ = _case(23, B, L, C, H, D, bq, cached=0)
+    got = _run(X, W, b, w.cache_flags, B, L, C, H, D, bq)
+    ref, ref_bits = oracle.gemm_q(X, W, b, w.cache_flags, bq, H, D)
+    _check(got, ref, ref_bits, w.cache_flags, bq, "gemm_q image-DiT")
