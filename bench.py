@@ -145,6 +145,35 @@ def main():
                                 copy_bytes=2 * ncached * w.block_q * w.D * 2)
         del Oc
         Q.copy_(up_bf16(w.Q)); K.copy_(up_bf16(w.K)); V.copy_(up_bf16(w.V))
+    if not args.no_extras:
+        # the step before attention (GEMM-Q, Section 3.5): 3072 channels -> 24 heads x 128, flags skip tiles
+        C = 3072
+        g = torch.Generator(device=dev); g.manual_seed(7)
+        Xp = torch.randn((w.B, w.L, C), device=dev, generator=g).to(torch.bfloat16)
+        Wp = (torch.randn((w.H * w.D, C), device=dev, generator=g) / C ** 0.5).to(torch.bfloat16)
+        gq = []
+        dense_ms = None
+        for frac in (0.0, 0.5, 0.8, 0.9):
+            fl = None if frac == 0 else (torch.rand((w.B, w.H, w.Tq), device=dev, generator=g) < frac).to(torch.uint8)
+            live = w.B * w.H * w.Tq if fl is None else int((fl == 0).sum())
+            for _ in range(2):
+                pkg.sparse_gemm_q(Xp, Wp, None, fl, O, w.block_q)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                pkg.sparse_gemm_q(Xp, Wp, None, fl, O, w.block_q)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 10
+            dense_ms = ms if dense_ms is None else dense_ms
+            gq.append(dict(cached_frac=1.0 - live / (w.B * w.H * w.Tq), ms=ms,
+                           tflops_on_computed_tiles=2.0 * w.block_q * w.D * C * live / ms / 1e9,
+                           speedup_vs_dense=dense_ms / ms, ideal_speedup=(w.B * w.H * w.Tq) / max(live, 1)))
+            log(f"gemm_q cached {gq[-1]['cached_frac']:.2f}: {ms:.3f} ms, {gq[-1]['tflops_on_computed_tiles']:.0f} TFLOP/s, "
+                f"{gq[-1]['speedup_vs_dense']:.2f}x (ideal {gq[-1]['ideal_speedup']:.2f}x)")
+        extra["gemm_q"] = gq
+        del Xp, Wp
     extra["dense_equiv_tops"] = head["dense_equiv_tops"]
     extra["sparsity"] = 1.0 - head["keep"]
     extra["plan_ms"] = head["plan_ms"]

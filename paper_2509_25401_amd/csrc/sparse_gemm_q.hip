@@ -97,10 +97,14 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
     const int r = (wave + u * NWAVES) * 8 + lane / 8;
     x_goff[u] = (unsigned)(r * row_pitch + (((lane % 8) ^ row_swizzle(r)) * 16));
   }
-  // per-lane LDS offsets of the operand reads: row l32 of a 32-row block, k-step ks
-  int op_off[kStepK / 16];
+  // per-lane LDS offsets of the operand reads: row l32 of this wave's first 32-row block, k-step ks
+  int w_off[kStepK / 16], x_off[kStepK / 16];
 #pragma unroll
-  for (int ks = 0; ks < kStepK / 16; ++ks) op_off[ks] = l32 * kRowB + (((2 * ks + half) ^ row_swizzle(l32)) * 16);
+  for (int ks = 0; ks < kStepK / 16; ++ks) {
+    const int o = l32 * kRowB + (((2 * ks + half) ^ row_swizzle(l32)) * 16);
+    w_off[ks] = wn * 64 * kRowB + o;
+    x_off[ks] = 2 * W_TILEB + wm * 64 * kRowB + o;
+  }
 
   auto issue = [&](int kstep, auto stage_c) {
     constexpr int stage = decltype(stage_c)::value;
@@ -124,23 +128,26 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
       for (int e = 0; e < 16; ++e) acc[a][c][e] = 0.f;
 
   auto compute = [&](auto stage_c) {
+    // the stage is a compile-time constant: every LDS address is a lane register plus an immediate.
+    // All 16 operand reads of the stage are issued before the first MFMA, which then only waits for
+    // its own two operands.
     constexpr int stage = decltype(stage_c)::value;
-    const char* wt = smem + stage * W_TILEB + (wn * 64) * kRowB;
-    const char* xt = smem + 2 * W_TILEB + stage * X_TILEB + (wm * 64) * kRowB;
-    __builtin_amdgcn_s_setprio(1);
+    bf16x8 wa[kStepK / 16][2], xb[kStepK / 16][2];
 #pragma unroll
     for (int ks = 0; ks < kStepK / 16; ++ks) {
-      bf16x8 wa[2], xb[2];
 #pragma unroll
-      for (int a = 0; a < 2; ++a) wa[a] = *(const bf16x8*)(wt + a * 32 * kRowB + op_off[ks]);
+      for (int a = 0; a < 2; ++a) wa[ks][a] = *(const bf16x8*)(smem + stage * W_TILEB + a * 32 * kRowB + w_off[ks]);
 #pragma unroll
-      for (int c = 0; c < 2; ++c) xb[c] = *(const bf16x8*)(xt + c * 32 * kRowB + op_off[ks]);
+      for (int c = 0; c < 2; ++c) xb[ks][c] = *(const bf16x8*)(smem + stage * X_TILEB + c * 32 * kRowB + x_off[ks]);
+    }
+    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int ks = 0; ks < kStepK / 16; ++ks)
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int c = 0; c < 2; ++c)
-          acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], xb[c], acc[a][c], 0, 0, 0);
-    }
+          acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[ks][a], xb[ks][c], acc[a][c], 0, 0, 0);
     __builtin_amdgcn_s_setprio(0);
   };
 
@@ -148,16 +155,21 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
   using S1 = std::integral_constant<int, 1>;
   const int nk = p.C / kStepK;
   issue(0, S0{});
-  for (int k = 0; k < nk; k += 2) {
+  int k = 0;
+  for (; k + 1 < nk; k += 2) {   // two stages per trip, one per LDS buffer
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the stage has landed
     __syncthreads();
-    if (k + 1 < nk) issue(k + 1, S1{});
+    issue(k + 1, S1{});
     compute(S0{});
-    if (k + 1 >= nk) break;
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     if (k + 2 < nk) issue(k + 2, S0{});
     compute(S1{});
+  }
+  if (k < nk) {                  // odd number of stages: the last one sits in buffer 0
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    compute(S0{});
   }
 
   // epilogue: lane holds token l32 (+32*c) and, per accumulator quad q4, head channels
