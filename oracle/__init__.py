@@ -5,13 +5,15 @@ key blocks, raw copy for cached query blocks) plus the symbol packing of Section
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
 package; the product package never does, and the two share no code.
 
-`gemm_q` is the same kind of restatement for the sparse query projection (Section 3.5).
+`gemm_q` and `gemm_o` are the same kind of restatement for the sparse query and output projections
+(Section 3.5).
 
 Parity status: every function here is pinned by the CPU test-suite (printed packing
 example, textbook dense attention, closed forms, brute force).  Numerical parity with
 the authors' own kernel is unpinned: the paper prints no attention outputs.
 """
 from .gemm_q import gemm_q, computed_flops as gemm_q_flops  # noqa: F401
+from .gemm_o import gemm_o, reduced_heads as gemm_o_segments, speedup_model as gemm_o_speedup_model  # noqa: F401
 from .reference import (  # noqa: F401
     pack_symbols,
     unpack_symbols,

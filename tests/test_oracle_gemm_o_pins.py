@@ -1,0 +1,95 @@
+"""Pins of the GEMM-O oracle (sparse output projection, Section 3.5, Equations 3-4)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_25401_amd import synth
+from helpers import bits_to_f64
+
+
+def _case(seed, B, H, L, D, C_out, bq, cached=0.4):
+    r = np.random.default_rng(seed)
+    O = synth.normal_bf16(r, (B, H, L, D))
+    W = synth.f32_to_bf16_bits((r.standard_normal((C_out, H * D)) / np.sqrt(H * D)).astype(np.float32))
+    bias = synth.normal_bf16(r, (C_out,))
+    flags = (r.random((B, H, L // bq)) < cached).astype(np.uint8)
+    return O, W, bias, flags
+
+
+def test_without_flags_it_is_the_plain_projection_of_the_concatenated_heads():
+    B, H, L, D, C_out, bq = 2, 3, 32, 8, 20, 16
+    O, W, bias, _ = _case(1, B, H, L, D, C_out, bq)
+    out, _ = oracle.gemm_o(O, W, bias, None, 0, None, bq)
+    concat = bits_to_f64(O).transpose(0, 2, 1, 3).reshape(B, L, H * D)      # token-major, heads side by side
+    ref = concat @ bits_to_f64(W).T + bits_to_f64(bias)
+    assert np.abs(out - ref).max() < 1e-12
+    none, _ = oracle.gemm_o(O, W, None, None, 1, None, bq)                   # nothing is cached: empty sum
+    assert (none == 0).all()
+
+
+def test_brute_force_loops_on_tiny_shapes():
+    B, H, L, D, C_out, bq = 1, 3, 8, 2, 5, 4
+    O, W, bias, flags = _case(2, B, H, L, D, C_out, bq, cached=0.5)
+    Of, Wf, bf = bits_to_f64(O), bits_to_f64(W), bits_to_f64(bias)
+    for select in (0, 1):
+        out, _ = oracle.gemm_o(O, W, bias, flags, select, None, bq)
+        for l in range(L):
+            for n in range(C_out):
+                acc = 0.0
+                for h in range(H):
+                    if int(flags[0, h, l // bq] != 0) != select:
+                        continue
+                    for d in range(D):
+                        acc += Of[0, h, l, d] * Wf[n, h * D + d]
+                assert abs(out[0, l, n] - (acc + bf[n])) < 1e-12
+
+
+def test_equation_3_the_two_head_sets_add_up_to_the_dense_projection():
+    B, H, L, D, C_out, bq = 2, 4, 48, 8, 12, 16
+    O, W, bias, flags = _case(3, B, H, L, D, C_out, bq)
+    dense, _ = oracle.gemm_o(O, W, None, None, 0, None, bq)
+    cached_part, _ = oracle.gemm_o(O, W, None, flags, 1, None, bq)
+    computed_part, _ = oracle.gemm_o(O, W, None, flags, 0, None, bq)
+    assert np.abs(cached_part + computed_part - dense).max() < 1e-12
+    assert np.abs(cached_part).max() > 0 and np.abs(computed_part).max() > 0
+
+
+def test_equation_4_cached_bias_reproduces_the_projection_when_cached_heads_do_not_change():
+    """Update step: B_c = stage 1.  Dispatch step: the cached heads' outputs are unchanged (identity reuse) and
+    the others are new; stage 2 with B_c equals the dense projection of the new tensor up to B_c's bf16 rounding."""
+    B, H, L, D, C_out, bq = 1, 4, 32, 8, 16, 16
+    O, W, bias, flags = _case(4, B, H, L, D, C_out, bq)
+    _, Bc_bits = oracle.gemm_o(O, W, None, flags, 1, None, bq)
+    O_new = synth.normal_bf16(np.random.default_rng(40), O.shape)
+    keep = np.repeat(flags != 0, bq, axis=2)[..., None]
+    O_new = np.where(keep, O, O_new)                       # cached heads carry over
+    out, _ = oracle.gemm_o(O_new, W, bias, flags, 0, Bc_bits, bq)
+    dense, _ = oracle.gemm_o(O_new, W, bias, None, 0, None, bq)
+    exact_bc, _ = oracle.gemm_o(O, W, None, flags, 1, None, bq)
+    assert np.abs(out - dense).max() <= np.abs(exact_bc).max() * 2.0 ** -8
+
+
+def test_one_hot_outputs_select_weight_entries():
+    B, H, L, D, C_out, bq = 1, 2, 16, 4, 6, 8
+    r = np.random.default_rng(5)
+    W = synth.normal_bf16(r, (C_out, H * D))
+    Of = np.zeros((B, H, L, D), dtype=np.float32)
+    Of[0, 1, np.arange(L), np.arange(L) % D] = 1.0          # only head 1 speaks
+    out, _ = oracle.gemm_o(synth.f32_to_bf16_bits(Of), W, None, None, 0, None, bq)
+    Wf = bits_to_f64(W)
+    for l in range(L):
+        assert (out[0, l] == Wf[:, 1 * D + l % D]).all()
+
+
+def test_speedup_model_matches_segment_accounting_and_the_printed_example():
+    assert oracle.gemm_o_speedup_model(6, 0.9) == pytest.approx(4.0)       # printed: N = 6, s = 0.9 -> 4x
+    B, H, Tq = 2, 8, 10
+    flags = np.zeros((B, H, Tq), dtype=np.uint8)
+    flags.reshape(-1)[: int(0.75 * flags.size)] = 1                         # s = 0.75 exactly
+    total = B * H * Tq
+    stage1 = oracle.gemm_o_segments(flags, 1, B, H, Tq)
+    stage2 = oracle.gemm_o_segments(flags, 0, B, H, Tq)
+    assert stage1 + stage2 == total
+    for N in (4, 6, 8):
+        work = (stage1 + stage2) + (N - 1) * stage2          # one Update step, N-1 Dispatch steps
+        assert N * total / work == pytest.approx(oracle.gemm_o_speedup_model(N, 0.75))
