@@ -173,7 +173,37 @@ def main():
             log(f"gemm_q cached {gq[-1]['cached_frac']:.2f}: {ms:.3f} ms, {gq[-1]['tflops_on_computed_tiles']:.0f} TFLOP/s, "
                 f"{gq[-1]['speedup_vs_dense']:.2f}x (ideal {gq[-1]['ideal_speedup']:.2f}x)")
         extra["gemm_q"] = gq
-        del Xp, Wp
+        del Xp
+        # the step after attention (GEMM-O stage 2, Section 3.5): heads whose flag is set are skipped along the
+        # reduction axis and their contribution comes from the cached bias B_c (the addend)
+        Wo = (torch.randn((C, w.H * w.D), device=dev, generator=g) / (w.H * w.D) ** 0.5).to(torch.bfloat16)
+        Bc = torch.randn((w.B, w.L, C), device=dev, generator=g).to(torch.bfloat16)
+        Yo = torch.empty((w.B, w.L, C), device=dev, dtype=torch.bfloat16)
+        go = []
+        dense_ms = None
+        for frac in (0.0, 0.5, 0.8, 0.9):
+            fl = None if frac == 0 else (torch.rand((w.B, w.H, w.Tq), device=dev, generator=g) < frac).to(torch.uint8)
+            live = w.B * w.H * w.Tq if fl is None else int((fl == 0).sum())
+            for _ in range(2):
+                pkg.sparse_gemm_o(Q, Wo, None, fl, 0, Bc, Yo, w.block_q)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                pkg.sparse_gemm_o(Q, Wo, None, fl, 0, Bc, Yo, w.block_q)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 10
+            dense_ms = ms if dense_ms is None else dense_ms
+            sfrac = 1.0 - live / (w.B * w.H * w.Tq)
+            go.append(dict(cached_frac=sfrac, ms=ms, tflops_on_visited_segments=2.0 * w.block_q * w.D * C * live / ms / 1e9,
+                           speedup_vs_dense=dense_ms / ms,
+                           aggregated_speedup_N6=6 * dense_ms / (dense_ms + 5 * ms),
+                           model_speedup_N6=6 / (1 + 5 * (1 - sfrac))))
+            log(f"gemm_o stage 2 cached {sfrac:.2f}: {ms:.3f} ms, {go[-1]['speedup_vs_dense']:.2f}x; over N=6 steps "
+                f"{go[-1]['aggregated_speedup_N6']:.2f}x (model {go[-1]['model_speedup_N6']:.2f}x)")
+        extra["gemm_o"] = go
+        del Wp, Wo, Bc, Yo
     extra["dense_equiv_tops"] = head["dense_equiv_tops"]
     extra["sparsity"] = 1.0 - head["keep"]
     extra["plan_ms"] = head["plan_ms"]

@@ -111,6 +111,33 @@ int sparse_gemm_q_stream(const void* X, const void* W, const void* bias, const u
                          int B, int L, int C, int H, int D, int block_q, void* hip_stream);
 
 /*
+ * Sparse output projection (GEMM-O, Section 3.5, Observation 3 / Equations 3-4): the step right after
+ * the attention call.  For every token block i and every output channel n
+ *     Out[b, token, n] = addend[b, token, n] + bias[n]
+ *                        + sum over heads h with (cache_flags[b,h,i] != 0) == select_cached of
+ *                          O[b, h, token, :] . W[n, h*D : (h+1)*D]
+ * The paper's two stages are two calls.  Stage 1, at an Update step: select_cached = 1, addend = NULL,
+ * bias = NULL; the result is the cached bias B_c, the part of the projection that comes from the heads
+ * whose attention output will be reused.  Stage 2, at every step: select_cached = 0, addend = B_c;
+ * heads whose flag is set are skipped along the reduction axis (their O and W columns are never
+ * loaded).  With cache_flags NULL no head counts as cached.
+ *   O            device, bf16 [B, H, L, D] (the attention output)
+ *   W            device, bf16 [C_out, H*D]: one row per output feature (Linear layer layout)
+ *   bias         device, bf16 [C_out], or NULL
+ *   cache_flags  device, uint8 [B, H, L/block_q] or NULL
+ *   addend       device, bf16 [B, L, C_out], NULL, or Out itself (accumulate in place)
+ *   Out          device, bf16 [B, L, C_out], written everywhere (fp32 accumulation, rounded to
+ *                nearest even); must not overlap O or W
+ * Supported: D and block_q in {64, 128}, H <= 64, C_out a multiple of 128, L a multiple of block_q.
+ * Errors as for sparse_attn_fwd.  Allocates nothing.
+ */
+int sparse_gemm_o(const void* O, const void* W, const void* bias, const uint8_t* cache_flags, int select_cached,
+                  const void* addend, void* Out, int B, int H, int L, int D, int C_out, int block_q);
+int sparse_gemm_o_stream(const void* O, const void* W, const void* bias, const uint8_t* cache_flags,
+                         int select_cached, const void* addend, void* Out, int B, int H, int L, int D, int C_out,
+                         int block_q, void* hip_stream);
+
+/*
  * Live kernel timing for benchmarks.  Between sparse_attn_profile_begin(max_calls) and
  * sparse_attn_profile_end(), each of the first max_calls calls of sparse_attn_fwd /
  * sparse_attn_fwd_stream records three HIP events on its own stream (start, after the symbol

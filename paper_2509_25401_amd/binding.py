@@ -52,6 +52,10 @@ def load_library():
     lib.sparse_gemm_q.restype = i32
     lib.sparse_gemm_q_stream.argtypes = [vp] * 5 + [i32] * 6 + [vp]
     lib.sparse_gemm_q_stream.restype = i32
+    lib.sparse_gemm_o.argtypes = [vp] * 4 + [i32, vp, vp] + [i32] * 6
+    lib.sparse_gemm_o.restype = i32
+    lib.sparse_gemm_o_stream.argtypes = [vp] * 4 + [i32, vp, vp] + [i32] * 6 + [vp]
+    lib.sparse_gemm_o_stream.restype = i32
     lib.sparse_attn_profile_begin.argtypes = [i32]
     lib.sparse_attn_profile_begin.restype = i32
     lib.sparse_attn_profile_end.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -141,6 +145,25 @@ def sparse_gemm_q(X, W, bias, cache_flags, Q, block_q, stream=None):
     if rc != 0:
         _raise(rc)
     return Q
+
+
+def sparse_gemm_o(O, W, bias, cache_flags, select_cached, addend, Out, block_q, stream=None):
+    """Sparse output projection on device tensors: O bf16 [B,H,L,D], W bf16 [C_out,H*D], bias bf16 [C_out] or None,
+    cache_flags uint8 [B,H,L/block_q] or None, addend bf16 [B,L,C_out] / None / Out, Out bf16 [B,L,C_out] (written).
+    select_cached = 1 sums the heads whose flag is set (stage 1, the cached bias), 0 the others (stage 2)."""
+    B, H, L, D = O.shape
+    C_out = W.shape[0]
+    if tuple(W.shape) != (C_out, H * D) or tuple(Out.shape) != (B, L, C_out):
+        raise ValueError("shapes of O [B,H,L,D], W [C_out,H*D] and Out [B,L,C_out] do not fit together")
+    if addend is not None and tuple(addend.shape) != (B, L, C_out):
+        raise ValueError("addend must have the shape of Out")
+    rc = load_library().sparse_gemm_o_stream(_dev_ptr(O, "O"), _dev_ptr(W, "W"), _dev_ptr(bias, "bias", True),
+                                             _dev_ptr(cache_flags, "cache_flags", True), int(select_cached),
+                                             _dev_ptr(addend, "addend", True), _dev_ptr(Out, "Out"),
+                                             int(B), int(H), int(L), int(D), int(C_out), int(block_q), _stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
+    return Out
 
 
 def sparse_attn_profile_begin(max_calls: int) -> None:

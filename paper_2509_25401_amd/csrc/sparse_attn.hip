@@ -180,27 +180,6 @@ __device__ __forceinline__ int v_swizzle(int row) {
   return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1);
 }
 
-// Direct-to-LDS load: every lane fetches 16 bytes from gbase (wave-uniform) + lane_off, the wave's
-// 1 KiB lands at consecutive LDS addresses starting at the wave-uniform `lds_addr`.  Written as
-// inline assembly so that the compiler does not serialise later LDS reads of the OTHER buffer
-// behind these loads (it cannot tell the two buffers apart); the kernel waits for them itself
-// (wait_vmem + barrier) before the buffer is read.
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void load_to_lds_16B(const char* gbase, unsigned lane_off, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_addr), "v"(lane_off), "s"(gbase)
-               : "memory", "m0");
-}
-#pragma clang diagnostic pop
-
-__device__ __forceinline__ void wait_vmem() {
-  // s_waitcnt vmcnt(0) only: expcnt and lgkmcnt fields left at their maxima
-  __builtin_amdgcn_s_waitcnt(0x0F70);
-}
-
-
 template <int D, int BQ, int BK>
 __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
   constexpr int NWAVES = BQ / 32;
@@ -355,8 +334,8 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
 #pragma unroll
       for (int t = 0; t < NLOAD; ++t) {
         const unsigned dst = (unsigned)(buf * TILEB + (wave + t * NWAVES) * 1024);
-        load_to_lds_16B(gK, k_goff[t], lds_base + dst);
-        load_to_lds_16B(gV, v_goff[t], lds_base + 2 * TILEB + dst);
+        sa_load_to_lds_16B(gK, k_goff[t], lds_base + dst);
+        sa_load_to_lds_16B(gV, v_goff[t], lds_base + 2 * TILEB + dst);
       }
     };
 
@@ -465,7 +444,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
         nsub = 0;
         nj = next_block();
       }
-      wait_vmem();
+      sa_wait_vmem();
       __syncthreads();   // this sub-tile has landed for every wave; the other buffer is free
       if (nj >= 0) issue_loads(nj, nsub, other);
       compute(cur);

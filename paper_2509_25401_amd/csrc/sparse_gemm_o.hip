@@ -1,0 +1,315 @@
+// Sparse output projection (GEMM-O of the paper, Section 3.5, Observation 3 / Equations 3-4) for gfx950.
+//
+// Out[b, token, n] = addend[b, token, n] + bias[n] + sum over SELECTED heads h of O[b,h,token,:] . W[n, h*D:(h+1)*D]
+// where, for the token block i the token lies in, head h is selected when its cache flag equals
+// `select`.  The paper's two stages are two calls: stage 1 at an Update step (select = flag set,
+// no addend) produces the cached bias B_c, the part of the projection that comes from heads whose
+// attention output is reused; stage 2 at every step (select = flag clear, addend = B_c) adds the
+// heads that were really computed.  The skipping is along the REDUCTION axis: the K loop of a tile
+// walks a bitmap of that token block's selected heads (built with one wave ballot, walked with
+// scalar find-first-set) and never loads the O or W columns of the others.
+//
+// One workgroup per (token block, 128 output channels) tile; transposed MFMA product as in the
+// query projection (A = weight rows, B = token rows, both k-contiguous in LDS), direct-to-LDS
+// loads, 64 reduction channels per stage, double buffered.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "sparse_attn.h"
+#include "sparse_attn_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+#define LDS_PTR(T) T __attribute__((address_space(3)))*
+
+constexpr int kStepK = 64;                 // reduction channels per LDS stage
+constexpr int kRowB = kStepK * 2;          // bytes per tile row in LDS
+constexpr int kBN = 128;                   // output channels per workgroup
+
+struct GemmOParams {
+  const char* O;         // bf16 [B, H, L, D]
+  const char* W;         // bf16 [C_out, H*D]
+  const uint16_t* bias;  // bf16 [C_out] or nullptr
+  const uint8_t* flags;  // [B, H, Tq] or nullptr
+  const char* addend;    // bf16 [B, L, C_out] or nullptr
+  char* Out;             // bf16 [B, L, C_out]
+  int H, L, Tq, C_out, select;
+};
+
+__device__ __forceinline__ int row_swizzle(int row) { return (row >> 1) & 7; }
+
+__device__ __forceinline__ float bf16_bits_to_float(unsigned bits16) {
+  return __builtin_bit_cast(float, bits16 << 16);
+}
+
+template <int BQ, int D>
+__global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const GemmOParams p) {
+  constexpr int WM = BQ / 64;              // waves along tokens
+  constexpr int WN = kBN / 64;             // waves along output channels
+  constexpr int NWAVES = WM * WN;
+  constexpr int PARTS = D / kStepK;        // stages per head
+  constexpr int W_TILEB = kBN * kRowB;
+  constexpr int X_TILEB = BQ * kRowB;
+  constexpr int W_LOAD = W_TILEB / 1024 / NWAVES;   // direct-to-LDS wave instructions per stage and wave
+  constexpr int X_LOAD = X_TILEB / 1024 / NWAVES;
+  static_assert((W_TILEB / 1024) % NWAVES == 0 && (X_TILEB / 1024) % NWAVES == 0, "stage loads must split evenly");
+
+  // column tile fastest: the 8 XCDs (workgroup n runs on XCD n mod 8) each keep the weight rows of a
+  // fixed set of column tiles in their L2 while the token blocks stream past
+  const int ncol = p.C_out / kBN;
+  const int t = blockIdx.x;
+  const int col = t % ncol;
+  const int i = (t / ncol) % p.Tq;
+  const int b = t / (ncol * p.Tq);
+
+  extern __shared__ __attribute__((aligned(1024))) char smem[];   // W stage 0, W stage 1, O stage 0, O stage 1
+  const unsigned lds_base = (unsigned)(uintptr_t)(LDS_PTR(char))smem;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WM, wn = wave / WM;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  // reduction-axis symbol of this token block: one bit per head, set = visit
+  unsigned long long heads;
+  {
+    bool mine = false;
+    if (lane < p.H) {
+      const int flag = p.flags ? (p.flags[((size_t)b * p.H + lane) * p.Tq + i] != 0) : 0;
+      mine = flag == p.select;
+    }
+    heads = __builtin_amdgcn_ballot_w64(mine);
+  }
+
+  const size_t w_pitch = (size_t)p.H * D * 2;
+  const char* gW = p.W + (size_t)col * kBN * w_pitch;
+  const char* gO = p.O + ((size_t)b * p.H * p.L + (size_t)i * BQ) * (size_t)(D * 2);   // head 0; head h adds h*L*D*2
+
+  unsigned w_goff[W_LOAD], x_goff[X_LOAD];
+#pragma unroll
+  for (int u = 0; u < W_LOAD; ++u) {
+    const int r = (wave + u * NWAVES) * 8 + lane / 8;
+    w_goff[u] = (unsigned)(r * w_pitch + (((lane % 8) ^ row_swizzle(r)) * 16));
+  }
+#pragma unroll
+  for (int u = 0; u < X_LOAD; ++u) {
+    const int r = (wave + u * NWAVES) * 8 + lane / 8;
+    x_goff[u] = (unsigned)(r * (D * 2) + (((lane % 8) ^ row_swizzle(r)) * 16));
+  }
+  int w_off[kStepK / 16], x_off[kStepK / 16];
+#pragma unroll
+  for (int ks = 0; ks < kStepK / 16; ++ks) {
+    const int o = l32 * kRowB + (((2 * ks + half) ^ row_swizzle(l32)) * 16);
+    w_off[ks] = wn * 64 * kRowB + o;
+    x_off[ks] = 2 * W_TILEB + wm * 64 * kRowB + o;
+  }
+
+  auto issue = [&](int h, int part, auto stage_c) {
+    constexpr int stage = decltype(stage_c)::value;
+    const char* w_src = gW + ((size_t)h * D + (size_t)part * kStepK) * 2;
+    const char* x_src = gO + (size_t)h * p.L * (D * 2) + (size_t)part * kRowB;
+#pragma unroll
+    for (int u = 0; u < W_LOAD; ++u)
+      sa_load_to_lds_16B(w_src, w_goff[u], lds_base + (unsigned)(stage * W_TILEB + (wave + u * NWAVES) * 1024));
+#pragma unroll
+    for (int u = 0; u < X_LOAD; ++u)
+      sa_load_to_lds_16B(x_src, x_goff[u],
+                         lds_base + (unsigned)(2 * W_TILEB + stage * X_TILEB + (wave + u * NWAVES) * 1024));
+  };
+
+  f32x16 acc[2][2];   // [output-channel block][token block] of this wave's 64x64 corner
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[a][c][e] = 0.f;
+
+  auto compute = [&](auto stage_c) {
+    constexpr int stage = decltype(stage_c)::value;
+    bf16x8 wa[kStepK / 16][2], xb[kStepK / 16][2];
+#pragma unroll
+    for (int ks = 0; ks < kStepK / 16; ++ks) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a) wa[ks][a] = *(const bf16x8*)(smem + stage * W_TILEB + a * 32 * kRowB + w_off[ks]);
+#pragma unroll
+      for (int c = 0; c < 2; ++c) xb[ks][c] = *(const bf16x8*)(smem + stage * X_TILEB + c * 32 * kRowB + x_off[ks]);
+    }
+    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int ks = 0; ks < kStepK / 16; ++ks)
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+          acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[ks][a], xb[ks][c], acc[a][c], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
+  };
+
+  // the addend (cached bias) of this lane's output elements is fetched now, so that its latency hides
+  // behind the reduction loop: [a][q4][c] -> 4 consecutive output channels of one token
+  const size_t token0 = (size_t)b * p.L + (size_t)i * BQ + wm * 64 + l32;
+  u32x2 add_bits[2][4][2];
+  if (p.addend) {
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const int n0 = col * kBN + wn * 64 + 32 * a + 8 * q4 + 4 * half;
+          add_bits[a][q4][c] = *(const u32x2*)(p.addend + ((token0 + (size_t)c * 32) * p.C_out + n0) * 2);
+        }
+  }
+
+  // scalar walk over the selected heads, PARTS stages per head
+  int h = heads ? __builtin_ctzll(heads) : -1;
+  int part = 0;
+  auto advance = [&](int& nh, int& npart) {
+    nh = h;
+    npart = part + 1;
+    if (npart == PARTS) {
+      npart = 0;
+      heads &= heads - 1ull;
+      nh = heads ? __builtin_ctzll(heads) : -1;
+    }
+  };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+  auto step = [&](auto cur, auto other) {
+    int nh, npart;
+    advance(nh, npart);
+    sa_wait_vmem();
+    __syncthreads();   // this stage has landed for every wave; the other buffer is free
+    if (nh >= 0) issue(nh, npart, other);
+    compute(cur);
+    h = nh;
+    part = npart;
+  };
+  if (h >= 0) issue(h, 0, S0{});
+  while (h >= 0) {
+    step(S0{}, S1{});
+    if (h < 0) break;
+    step(S1{}, S0{});
+  }
+
+  // epilogue: lane holds token l32 (+32*c) and, per accumulator quad q4, output channels
+  // 32*a + 8*q4 + 4*half + 0..3 of this wave's corner
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int n0 = col * kBN + wn * 64 + 32 * a + 8 * q4 + 4 * half;
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (p.bias) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bv[e] = bf16_bits_to_float(p.bias[n0 + e]);
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const size_t off = ((token0 + (size_t)c * 32) * p.C_out + n0) * 2;
+        float add[4] = {bv[0], bv[1], bv[2], bv[3]};
+        if (p.addend) {
+          const u32x2 ad = add_bits[a][q4][c];
+          add[0] += bf16_bits_to_float(ad[0] & 0xffffu);
+          add[1] += bf16_bits_to_float(ad[0] >> 16);
+          add[2] += bf16_bits_to_float(ad[1] & 0xffffu);
+          add[3] += bf16_bits_to_float(ad[1] >> 16);
+        }
+        bf16x2 lo, hi;
+        lo[0] = (__bf16)(acc[a][c][4 * q4 + 0] + add[0]);
+        lo[1] = (__bf16)(acc[a][c][4 * q4 + 1] + add[1]);
+        hi[0] = (__bf16)(acc[a][c][4 * q4 + 2] + add[2]);
+        hi[1] = (__bf16)(acc[a][c][4 * q4 + 3] + add[3]);
+        u32x2 pk;
+        pk[0] = __builtin_bit_cast(unsigned, lo);
+        pk[1] = __builtin_bit_cast(unsigned, hi);
+        *(u32x2*)(p.Out + off) = pk;
+      }
+    }
+}
+
+template <int BQ, int D>
+int launch(const GemmOParams& p, int tiles, hipStream_t stream) {
+  constexpr size_t lds = 2 * (size_t)(kBN + BQ) * kRowB;
+  constexpr int threads = (BQ / 64) * 2 * 64;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_o_kernel<BQ, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    if (e != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_o_kernel<BQ, D>), dim3(tiles), dim3(threads), lds, stream, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "gemm_o launch failed: %s", hipGetErrorString(e));
+  return 0;
+}
+
+bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
+  const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + nb && y < x + na;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sparse_gemm_o_stream(const void* O, const void* W, const void* bias, const uint8_t* cache_flags,
+                         int select_cached, const void* addend, void* Out, int B, int H, int L, int D, int C_out,
+                         int block_q, void* hip_stream) {
+  if (B <= 0 || H <= 0 || L <= 0 || D <= 0 || C_out <= 0 || block_q <= 0)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: sizes must be positive (B=%d H=%d L=%d D=%d C_out=%d block_q=%d)",
+                   B, H, L, D, C_out, block_q);
+  if (select_cached != 0 && select_cached != 1)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: select_cached must be 0 or 1 (got %d)", select_cached);
+  if ((D != 64 && D != 128) || (block_q != 64 && block_q != 128))
+    return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_o: D and block_q must be 64 or 128 (got %d, %d)", D, block_q);
+  if (H > 64) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_o: at most 64 heads (got %d)", H);
+  if (C_out % kBN)
+    return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_o: C_out=%d must be a multiple of %d", C_out, kBN);
+  if (L % block_q) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: L=%d must be a multiple of block_q=%d", L, block_q);
+  if ((long long)kBN * H * D * 2 >= (1LL << 31)) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_o: H*D too large");
+  const long long tiles = (long long)B * (L / block_q) * (C_out / kBN);
+  if (tiles > 0x3fffffffLL) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_o: too many tiles (%lld)", tiles);
+  if (!O || !W || !Out) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: O, W and Out must not be NULL");
+  if (((uintptr_t)O | (uintptr_t)W | (uintptr_t)Out | (uintptr_t)addend) & 15)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: O, W, addend and Out must be 16-byte aligned");
+  const size_t ob = (size_t)B * H * L * D * 2, wb = (size_t)C_out * H * D * 2, outb = (size_t)B * L * C_out * 2;
+  if (ranges_overlap(Out, outb, O, ob) || ranges_overlap(Out, outb, W, wb))
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: Out must not overlap O or W");
+  if (addend && addend != Out && ranges_overlap(Out, outb, addend, outb))
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: addend must be Out itself or must not overlap Out");
+
+  GemmOParams p;
+  p.O = (const char*)O;
+  p.W = (const char*)W;
+  p.bias = (const uint16_t*)bias;
+  p.flags = cache_flags;
+  p.addend = (const char*)addend;
+  p.Out = (char*)Out;
+  p.H = H;
+  p.L = L;
+  p.Tq = L / block_q;
+  p.C_out = C_out;
+  p.select = select_cached;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (block_q == 128 && D == 128) return launch<128, 128>(p, (int)tiles, stream);
+  if (block_q == 128 && D == 64) return launch<128, 64>(p, (int)tiles, stream);
+  if (block_q == 64 && D == 128) return launch<64, 128>(p, (int)tiles, stream);
+  return launch<64, 64>(p, (int)tiles, stream);
+}
+
+int sparse_gemm_o(const void* O, const void* W, const void* bias, const uint8_t* cache_flags, int select_cached,
+                  const void* addend, void* Out, int B, int H, int L, int D, int C_out, int block_q) {
+  return sparse_gemm_o_stream(O, W, bias, cache_flags, select_cached, addend, Out, B, H, L, D, C_out, block_q, nullptr);
+}
+
+}  // extern "C"

@@ -41,16 +41,6 @@ struct GemmQParams {
 // 16-byte chunk permutation of a 128-byte tile row (two rows share a 256-byte bank line)
 __device__ __forceinline__ int row_swizzle(int row) { return (row >> 1) & 7; }
 
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void gq_load_to_lds_16B(const char* gbase, unsigned lane_off, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_addr), "v"(lane_off), "s"(gbase)
-               : "memory", "m0");
-}
-#pragma clang diagnostic pop
-
 template <int BQ, int D>
 __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(const GemmQParams p) {
   constexpr int WM = BQ / 64;              // waves along tokens
@@ -112,10 +102,10 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
     const char* x_src = gX + (size_t)kstep * kRowB;
 #pragma unroll
     for (int u = 0; u < W_LOAD; ++u)
-      gq_load_to_lds_16B(w_src, w_goff[u], lds_base + (unsigned)(stage * W_TILEB + (wave + u * NWAVES) * 1024));
+      sa_load_to_lds_16B(w_src, w_goff[u], lds_base + (unsigned)(stage * W_TILEB + (wave + u * NWAVES) * 1024));
 #pragma unroll
     for (int u = 0; u < X_LOAD; ++u)
-      gq_load_to_lds_16B(x_src, x_goff[u],
+      sa_load_to_lds_16B(x_src, x_goff[u],
                          lds_base + (unsigned)(2 * W_TILEB + stage * X_TILEB + (wave + u * NWAVES) * 1024));
   };
 
@@ -157,17 +147,17 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
   issue(0, S0{});
   int k = 0;
   for (; k + 1 < nk; k += 2) {   // two stages per trip, one per LDS buffer
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the stage has landed
+    sa_wait_vmem();   // this wave's part of the stage has landed
     __syncthreads();
     issue(k + 1, S1{});
     compute(S0{});
-    __builtin_amdgcn_s_waitcnt(0x0F70);
+    sa_wait_vmem();
     __syncthreads();
     if (k + 2 < nk) issue(k + 2, S0{});
     compute(S1{});
   }
   if (k < nk) {                  // odd number of stages: the last one sits in buffer 0
-    __builtin_amdgcn_s_waitcnt(0x0F70);
+    sa_wait_vmem();
     __syncthreads();
     compute(S0{});
   }

@@ -29,7 +29,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = pkg.load_library()
     names = _declared_functions()
-    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and len(names) >= 10
+    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and "sparse_gemm_o" in names and len(names) >= 12
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
     assert pkg.sparse_attn_version() >= 100
@@ -112,4 +112,23 @@ def _gemm_q(B=1, L=128, C=64, H=1, D=128, bq=128, X=FAKE, W=ctypes.c_void_p(0x20
 ])
 def test_gemm_q_argument_validation_precedes_any_device_work(kw, code):
     assert _gemm_q(**kw) == code
+    assert pkg.sparse_attn_last_error() != ""
+
+
+def _gemm_o(B=1, H=2, L=128, D=128, C_out=128, bq=128, sel=0, O=FAKE, W=ctypes.c_void_p(0x20000000),
+            addend=None, Out=ctypes.c_void_p(0x90000000)):
+    return pkg.load_library().sparse_gemm_o(O, W, None, None, sel, addend, Out, B, H, L, D, C_out, bq)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(B=0), -1), (dict(H=0), -1), (dict(L=0), -1), (dict(D=0), -1), (dict(C_out=0), -1), (dict(bq=0), -1),
+    (dict(sel=2), -1), (dict(L=192), -1),
+    (dict(C_out=192), -2), (dict(D=96), -2), (dict(bq=32), -2), (dict(H=65), -2),
+    (dict(O=None), -1), (dict(W=None), -1), (dict(Out=None), -1),
+    (dict(Out=FAKE), -1),                                   # Out aliases O
+    (dict(addend=ctypes.c_void_p(0x90000000 + 64)), -1),    # addend overlaps Out without being Out
+    (dict(O=ctypes.c_void_p(0x10004)), -1),
+])
+def test_gemm_o_argument_validation_precedes_any_device_work(kw, code):
+    assert _gemm_o(**kw) == code
     assert pkg.sparse_attn_last_error() != ""

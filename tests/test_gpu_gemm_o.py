@@ -1,0 +1,97 @@
+"""GPU parity of the sparse output projection (GEMM-O) against its CPU oracle.
+
+Bar per element: |got - ref| <= 2^-8 |ref| + 2e-3 (one bf16 rounding of the result; fp32 accumulation of
+up to 3072 products of O(1) terms and the bf16 addend contribute well below the absolute term)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_25401_amd as pkg
+from paper_2509_25401_amd import synth
+from gpu_utils import up_bf16, up_u8, down_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(seed, B, H, L, D, C_out, bq, cached):
+    r = np.random.default_rng(seed)
+    O = synth.normal_bf16(r, (B, H, L, D))
+    W = synth.f32_to_bf16_bits((r.standard_normal((C_out, H * D)) / np.sqrt(H * D)).astype(np.float32))
+    bias = synth.normal_bf16(r, (C_out,))
+    flags = (r.random((B, H, L // bq)) < cached).astype(np.uint8) if cached is not None else None
+    return O, W, bias, flags
+
+
+def _run(O, W, bias, flags, select, addend, bq, in_place=False):
+    B, H, L, D = O.shape
+    C_out = W.shape[0]
+    Out = torch.from_numpy(np.full((B, L, C_out), 0x4242, dtype=np.uint16).view(np.int16)).view(torch.bfloat16).to("cuda:0")
+    ad = None if addend is None else up_bf16(addend)
+    if in_place:
+        Out.copy_(ad)
+        ad = Out
+    pkg.sparse_gemm_o(up_bf16(O), up_bf16(W), None if bias is None else up_bf16(bias), up_u8(flags), select, ad, Out, bq)
+    torch.cuda.synchronize()
+    return down_bits(Out)
+
+
+def _check(got_bits, ref, ref_bits, label):
+    got = synth.bf16_bits_to_f32(got_bits).astype(np.float64)
+    err = np.abs(got - ref)
+    tol = np.abs(ref) * 2.0 ** -8 + 2e-3
+    exact = (got_bits == ref_bits).mean()
+    print(f"[parity] {label}: max-abs {err.max():.3e}, bit-identical to the rounded oracle: {exact * 100:.2f}%", flush=True)
+    assert (err <= tol).all(), f"{label}: max violation {(err - tol).max()}"
+    assert exact > 0.97
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("bq", [64, 128])
+def test_both_stages_small_cases_all_variants(D, bq):
+    print(f"[case] gemm_o small D={D} bq={bq}", flush=True)
+    B, H, L, C_out = 2, 5, 384, 256
+    O, W, bias, flags = _case(30 + D + bq, B, H, L, D, C_out, bq, cached=0.4)
+    flags[0, :, 0] = 1            # a token block with every head cached: stage 2 is addend + bias only
+    flags[1, :, 1] = 0            # and one with none cached: stage 1 is zero
+    # stage 1: cached bias
+    got1 = _run(O, W, None, flags, 1, None, bq)
+    ref1, ref1_bits = oracle.gemm_o(O, W, None, flags, 1, None, bq)
+    _check(got1, ref1, ref1_bits, f"gemm_o stage1 D={D} bq={bq}")
+    assert (got1[1, bq:2 * bq] == 0).all()
+    # stage 2 on top of the kernel's own cached bias
+    got2 = _run(O, W, bias, flags, 0, got1, bq)
+    ref2, ref2_bits = oracle.gemm_o(O, W, bias, flags, 0, got1, bq)
+    _check(got2, ref2, ref2_bits, f"gemm_o stage2 D={D} bq={bq}")
+    # in place: addend == Out
+    assert (_run(O, W, bias, flags, 0, got1, bq, in_place=True) == got2).all()
+    # Equation 3: both stages together reproduce the dense projection (up to the bf16 rounding of B_c)
+    dense, _ = oracle.gemm_o(O, W, bias, None, 0, None, bq)
+    err = np.abs(synth.bf16_bits_to_f32(got2).astype(np.float64) - dense)
+    assert (err <= np.abs(dense) * 2.0 ** -8 + np.abs(ref1).max() * 2.0 ** -8 + 2e-3).all()
+
+
+def test_dense_without_flags_and_poisoned_skipped_heads():
+    print("[case] gemm_o dense / poison", flush=True)
+    B, H, L, D, C_out, bq = 1, 6, 256, 128, 384, 128
+    O, W, bias, flags = _case(40, B, H, L, D, C_out, bq, cached=0.5)
+    got = _run(O, W, bias, None, 0, None, bq)
+    ref, ref_bits = oracle.gemm_o(O, W, bias, None, 0, None, bq)
+    _check(got, ref, ref_bits, "gemm_o dense")
+    # NaN in every O block that stage 2 must skip: the result stays finite and unchanged
+    clean = _run(O, W, bias, flags, 0, None, bq)
+    Op = O.copy()
+    skip = np.repeat(flags != 0, bq, axis=2)
+    Op[skip] = 0x7FC0
+    assert (_run(Op, W, bias, flags, 0, None, bq) == clean).all()
+
+
+def test_image_dit_shape_stage2_with_config3_flags():
+    print("[case] gemm_o image-DiT shape", flush=True)
+    w = synth.config_image_cache_skip()
+    B, H, L, D, C_out, bq = 1, w.H, w.L, w.D, 3072, w.block_q
+    O, W, bias, _ = _case(41, B, H, L, D, C_out, bq, cached=None)
+    Bc = synth.normal_bf16(np.random.default_rng(42), (B, L, C_out))
+    got = _run(O, W, bias, w.cache_flags, 0, Bc, bq)
+    ref, ref_bits = oracle.gemm_o(O, W, bias, w.cache_flags, 0, Bc, bq)
+    _check(got, ref, ref_bits, "gemm_o image-DiT stage2")
