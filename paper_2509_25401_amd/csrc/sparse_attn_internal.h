@@ -22,6 +22,14 @@ __device__ __forceinline__ void sa_load_to_lds_16B(const char* gbase, unsigned l
 }
 #pragma clang diagnostic pop
 
+// A wave-uniform pointer that the compiler may have left in vector registers, moved to scalar registers.
+__device__ __forceinline__ const char* sa_uniform_ptr(const char* ptr) {
+  const unsigned long long v = (unsigned long long)ptr;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return (const char*)(((unsigned long long)hi << 32) | lo);
+}
+
 // s_waitcnt vmcnt(0) only: expcnt and lgkmcnt fields left at their maxima
 __device__ __forceinline__ void sa_wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 

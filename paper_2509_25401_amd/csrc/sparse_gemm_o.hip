@@ -26,6 +26,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 #define LDS_PTR(T) T __attribute__((address_space(3)))*
 
@@ -153,20 +155,21 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
     __builtin_amdgcn_s_setprio(0);
   };
 
-  // the addend (cached bias) of this lane's output elements is fetched now, so that its latency hides
-  // behind the reduction loop: [a][q4][c] -> 4 consecutive output channels of one token
-  const size_t token0 = (size_t)b * p.L + (size_t)i * BQ + wm * 64 + l32;
-  u32x2 add_bits[2][4][2];
+  // Output side.  The result tile leaves through LDS so that a lane writes 16 contiguous bytes of a
+  // token's row (and reads the addend the same way): thread -> (token, group of 8 output channels).
+  constexpr int NT = NWAVES * 64;
+  constexpr int OUT_ITERS = BQ * 16 / NT;
+  const int out_g = tid % 16;              // 8-channel group inside the 128-channel tile
+  const size_t out_row0 = (size_t)b * p.L + (size_t)i * BQ;
+  auto out_offset = [&](int it) -> size_t {
+    const int token = it * (NT / 16) + tid / 16;
+    return ((out_row0 + token) * p.C_out + col * kBN + out_g * 8) * 2;
+  };
+  // the addend (cached bias) is fetched now, so that its latency hides behind the reduction loop
+  u32x4 add_bits[OUT_ITERS];
   if (p.addend) {
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4)
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const int n0 = col * kBN + wn * 64 + 32 * a + 8 * q4 + 4 * half;
-          add_bits[a][q4][c] = *(const u32x2*)(p.addend + ((token0 + (size_t)c * 32) * p.C_out + n0) * 2);
-        }
+    for (int it = 0; it < OUT_ITERS; ++it) add_bits[it] = *(const u32x4*)(p.addend + out_offset(it));
   }
 
   // scalar walk over the selected heads, PARTS stages per head
@@ -200,40 +203,58 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
     step(S1{}, S0{});
   }
 
-  // epilogue: lane holds token l32 (+32*c) and, per accumulator quad q4, output channels
-  // 32*a + 8*q4 + 4*half + 0..3 of this wave's corner
+  // epilogue, part 1: the accumulators (lane = token l32 + 32*c, registers = output channels
+  // 32*a + 8*q4 + 4*half + 0..3 of this wave's corner) go to LDS as fp32 rows of 512 bytes, 16-byte
+  // chunks XOR-permuted by the token so that the 32 tokens of a store hit different banks
+  __syncthreads();   // every wave is done reading the stage buffers
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const int n0 = col * kBN + wn * 64 + 32 * a + 8 * q4 + 4 * half;
-      float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (p.bias) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) bv[e] = bf16_bits_to_float(p.bias[n0 + e]);
-      }
+    for (int q4 = 0; q4 < 4; ++q4)
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        const size_t off = ((token0 + (size_t)c * 32) * p.C_out + n0) * 2;
-        float add[4] = {bv[0], bv[1], bv[2], bv[3]};
-        if (p.addend) {
-          const u32x2 ad = add_bits[a][q4][c];
-          add[0] += bf16_bits_to_float(ad[0] & 0xffffu);
-          add[1] += bf16_bits_to_float(ad[0] >> 16);
-          add[2] += bf16_bits_to_float(ad[1] & 0xffffu);
-          add[3] += bf16_bits_to_float(ad[1] >> 16);
-        }
-        bf16x2 lo, hi;
-        lo[0] = (__bf16)(acc[a][c][4 * q4 + 0] + add[0]);
-        lo[1] = (__bf16)(acc[a][c][4 * q4 + 1] + add[1]);
-        hi[0] = (__bf16)(acc[a][c][4 * q4 + 2] + add[2]);
-        hi[1] = (__bf16)(acc[a][c][4 * q4 + 3] + add[3]);
-        u32x2 pk;
-        pk[0] = __builtin_bit_cast(unsigned, lo);
-        pk[1] = __builtin_bit_cast(unsigned, hi);
-        *(u32x2*)(p.Out + off) = pk;
+        const int token = wm * 64 + 32 * c + l32;
+        const int chunk = wn * 16 + 8 * a + 2 * q4 + half;
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[a][c][4 * q4 + e];
+        *(f32x4*)(smem + token * 512 + ((chunk ^ (token & 31)) * 16)) = v;
+      }
+  __syncthreads();
+  // part 2: row-contiguous read back, + addend + bias, round to bf16, 16-byte stores
+  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (p.bias) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bv[e] = bf16_bits_to_float(p.bias[col * kBN + out_g * 8 + e]);
+  }
+#pragma unroll
+  for (int it = 0; it < OUT_ITERS; ++it) {
+    const int token = it * (NT / 16) + tid / 16;
+    const f32x4 v0 = *(const f32x4*)(smem + token * 512 + (((2 * out_g) ^ (token & 31)) * 16));
+    const f32x4 v1 = *(const f32x4*)(smem + token * 512 + (((2 * out_g + 1) ^ (token & 31)) * 16));
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[e] = v0[e] + bv[e];
+      v[4 + e] = v1[e] + bv[4 + e];
+    }
+    if (p.addend) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[2 * e] += bf16_bits_to_float(add_bits[it][e] & 0xffffu);
+        v[2 * e + 1] += bf16_bits_to_float(add_bits[it][e] >> 16);
       }
     }
+    u32x4 pk;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      bf16x2 pr;
+      pr[0] = (__bf16)v[2 * e];
+      pr[1] = (__bf16)v[2 * e + 1];
+      pk[e] = __builtin_bit_cast(unsigned, pr);
+    }
+    *(u32x4*)(p.Out + out_offset(it)) = pk;
+  }
 }
 
 template <int BQ, int D>
