@@ -251,3 +251,17 @@ def config_video_sweep(keep: float, skewed: bool = False, H: Optional[int] = Non
     name = f"video-sweep-{keep:g}" + ("-skewed" if skewed else "")
     return Workload(name, B, H, L, D, bq, bk, Q, K, V, M, None, None,
                     {"text_blocks": nt, "target_keep": keep, "skewed": skewed})
+
+
+def structured_qk(seed, B, H, L, D, block, signal=1.2):
+    """Q, K with block-level structure, for the symbol generation of an Update step: every block of `block`
+    tokens shares a random direction of strength `signal` on top of N(0,1) noise, so that the mean-pooled
+    attention map has logits of O(1) spread (pure noise pools to an almost uniform map)."""
+    r = [np.random.default_rng(s) for s in np.random.SeedSequence(seed).spawn(4)]
+    T = L // block
+    out = []
+    for k in range(2):
+        mu = (signal * r[k].standard_normal((B, H, T, 1, D), dtype=np.float32))
+        x = r[2 + k].standard_normal((B, H, T, block, D), dtype=np.float32) + mu
+        out.append(f32_to_bf16_bits(x.reshape(B, H, L, D)))
+    return out[0], out[1]

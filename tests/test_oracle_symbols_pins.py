@@ -1,0 +1,114 @@
+"""Pins of the symbol-generation oracle (Section 3.3, Equation 1, settings table of the appendix)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_25401_amd import synth
+from helpers import bits_to_f64
+
+
+def test_brute_force_loops_on_a_tiny_case():
+    B, H, L, D, blk, text = 1, 2, 12, 4, 2, 4          # T = 6 blocks, 2 of them text
+    Q, K = synth.structured_qk(1, B, H, L, D, blk)
+    tau_c, tau_kv = 0.45, 0.3
+    out = oracle.update_symbols(Q, K, blk, text, tau_c, tau_kv)
+    Qf, Kf = bits_to_f64(Q), bits_to_f64(K)
+    T, nt = L // blk, text // blk
+    for h in range(H):
+        qt = [[sum(Qf[0, h, i * blk + r, d] for r in range(blk)) / blk for d in range(D)] for i in range(T)]
+        kt = [[sum(Kf[0, h, i * blk + r, d] for r in range(blk)) / blk for d in range(D)] for i in range(T)]
+        P = []
+        for i in range(T):
+            s = [sum(qt[i][d] * kt[j][d] for d in range(D)) / np.sqrt(D) for j in range(T)]
+            m = max(s)
+            e = [np.exp(x - m) for x in s]
+            P.append([x / sum(e) for x in e])
+        C = [sum(P[j][nt + v] for j in range(nt)) for v in range(T - nt)]
+        beta = []
+        for j in range(nt):
+            col = [P[nt + v][j] for v in range(T - nt)]
+            m = max(col)
+            e = [np.exp(x - m) for x in col]
+            beta.append([x / sum(e) for x in e])
+        G = [sum(beta[j][v] for j in range(nt)) for v in range(T - nt)]
+
+        def cum_up(x):
+            order = sorted(range(len(x)), key=lambda t: (x[t], t))
+            cs, run = [0.0] * len(x), 0.0
+            for t in order:
+                run += x[t]
+                cs[t] = run
+            return cs
+        cC, cG = cum_up(C), cum_up(G)
+        for v in range(T - nt):
+            want = int(cC[v] <= tau_c * sum(C) and cG[v] <= tau_c * sum(G))
+            assert out["cache_flags"][0, h, nt + v] == want
+        assert (out["cache_flags"][0, h, :nt] == 0).all()
+        for i in range(T):
+            cs = cum_up(P[i])
+            for j in range(T):
+                assert out["M_s"][0, h, i, j] == int(cs[j] > tau_kv)
+        assert np.abs(out["own_value"][0, h] - np.array(P)).max() < 1e-14
+
+
+def test_uniform_map_closed_form():
+    """Q = 0: P~ = 1/T everywhere, all metrics tie, ties go by index: the first floor(tau * count) entries are taken."""
+    B, H, L, D, blk, text = 1, 1, 160, 8, 8, 32       # T = 20, n_t = 4, 16 vision blocks
+    Q = np.zeros((B, H, L, D), dtype=np.uint16)
+    _, K = synth.structured_qk(2, B, H, L, D, blk)
+    out = oracle.update_symbols(Q, K, blk, text, 0.33, 0.27)
+    flags = out["cache_flags"][0, 0]
+    assert flags[:4].sum() == 0 and flags[4:].tolist() == [1] * 5 + [0] * 11      # floor(0.33 * 16) = 5
+    for i in range(20):
+        assert out["M_s"][0, 0, i].tolist() == [0] * 5 + [1] * 15                   # floor(0.27 * 20) = 5 skipped
+
+
+def test_thresholds_zero_and_one_and_monotonicity():
+    B, H, L, D, blk, text = 1, 2, 256, 16, 16, 32
+    Q, K = synth.structured_qk(3, B, H, L, D, blk)
+    nt = text // blk
+    lo = oracle.update_symbols(Q, K, blk, text, 0.0, 0.0)
+    assert lo["cache_flags"].sum() == 0 and (lo["M_s"] == 1).all()
+    hi = oracle.update_symbols(Q, K, blk, text, 1.0, 0.5)
+    assert (hi["cache_flags"][..., nt:] == 1).all() and (hi["cache_flags"][..., :nt] == 0).all()
+    prev_f, prev_m = lo["cache_flags"], lo["M_s"]
+    for tau in (0.2, 0.4, 0.6, 0.8):
+        cur = oracle.update_symbols(Q, K, blk, text, tau, tau)
+        assert (cur["cache_flags"] >= prev_f).all()          # cached set grows with tau_c
+        assert (cur["M_s"] <= prev_m).all()                  # kept set shrinks with tau_kv
+        kept_mass = (cur["own_value"] * cur["M_s"]).sum(axis=-1)
+        assert (kept_mass >= 1 - tau - 1e-12).all()          # skipped importance never exceeds tau_kv
+        assert (cur["M_s"].sum(axis=-1) >= 1).all()          # the largest entry of a row is always kept
+        prev_f, prev_m = cur["cache_flags"], cur["M_s"]
+
+
+def test_metrics_follow_their_definitions_on_a_hand_made_map():
+    P = np.array([[0.7, 0.1, 0.1, 0.1],      # text row
+                  [0.2, 0.5, 0.2, 0.1],
+                  [0.6, 0.2, 0.1, 0.1],
+                  [0.1, 0.1, 0.1, 0.7]])
+    C, G = oracle.caching_metrics(P, 1)
+    assert np.allclose(C, [0.1, 0.1, 0.1])                                    # text row's weights on the three vision blocks
+    e = np.exp(np.array([0.2, 0.6, 0.1]))
+    assert np.allclose(G, e / e.sum())                                        # softmax over vision blocks of their weight on text
+    assert np.argmax(G) == 1                                                  # the block that listens to text most is guided most
+
+
+def test_degrade_rule_and_block_permutation():
+    B, H, L, D, blk, text = 1, 1, 256, 16, 16, 32
+    Q, K = synth.structured_qk(4, B, H, L, D, blk)
+    T, nt = L // blk, text // blk
+    base = oracle.update_symbols(Q, K, blk, text, 0.7, 0.2)
+    need = (T - base["cache_flags"].sum()) / T
+    assert 0 < need < 1
+    off = oracle.update_symbols(Q, K, blk, text, 0.7, 0.2, s_q=need - 1e-6)
+    on = oracle.update_symbols(Q, K, blk, text, 0.7, 0.2, s_q=need + 1e-6)
+    assert (off["cache_flags"] == base["cache_flags"]).all() and (on["cache_flags"] == 1).all()
+    # permuting vision blocks (queries and keys together) permutes the symbols
+    perm = np.concatenate([np.arange(nt), nt + np.random.default_rng(5).permutation(T - nt)])
+    def blocks(x):
+        return np.ascontiguousarray(x.reshape(B, H, T, blk, D)[:, :, perm].reshape(x.shape))
+    p = oracle.update_symbols(blocks(Q), blocks(K), blk, text, 0.7, 0.2)
+    robust = ~base["flag_tie"][0, 0] & (base["flag_margin"][0, 0] > 1e-9)
+    assert (p["cache_flags"][0, 0][robust[perm]] == base["cache_flags"][0, 0][perm][robust[perm]]).all()
+    assert (p["M_s"][0, 0] == base["M_s"][0, 0][perm][:, perm]).mean() > 0.999
