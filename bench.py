@@ -204,6 +204,33 @@ def main():
                 f"{go[-1]['aggregated_speedup_N6']:.2f}x (model {go[-1]['model_speedup_N6']:.2f}x)")
         extra["gemm_o"] = go
         del Wp, Wo, Bc, Yo
+        # the symbol generation of an Update step (Section 3.3): reads Q and K once, writes both symbol arrays
+        text_tokens = 2 * w.block_q
+        fl = torch.empty((w.B, w.H, w.Tq), dtype=torch.uint8, device=dev)
+        mk = torch.empty((w.B, w.H, w.Tq, (w.Tq + 7) // 8), dtype=torch.uint8, device=dev)
+        # block-structured K (a shared direction per block) so that the pooled map is not uniform
+        Ks = (V.view(w.B, w.H, w.Tq, w.block_q, w.D).float()
+              + 1.2 * torch.randn((w.B, w.H, w.Tq, 1, w.D), device=dev, generator=g)).to(torch.bfloat16).view(Q.shape)
+        Qs = (K.view(w.B, w.H, w.Tq, w.block_q, w.D).float()
+              + 1.2 * torch.randn((w.B, w.H, w.Tq, 1, w.D), device=dev, generator=g)).to(torch.bfloat16).view(Q.shape)
+        for _ in range(2):
+            pkg.sparse_symbols_update(Qs, Ks, fl, mk, w.block_q, text_tokens, 0.5, 0.75)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            pkg.sparse_symbols_update(Qs, Ks, fl, mk, w.block_q, text_tokens, 0.5, 0.75)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        sym_bytes = 2 * Q.numel() * 2
+        keep_frac = float(sum(bin(x).count("1") for x in mk.cpu().numpy().reshape(-1).tolist())) / (w.B * w.H * w.Tq * w.Tkv)
+        extra["symbols_update"] = dict(ms=ms, hbm_bytes=sym_bytes, gbps=sym_bytes / ms / 1e6, frac_of_hbm_peak=sym_bytes / ms / 1e6 / 8000.0,
+                                       cached_frac=float(fl.float().mean()), keep_frac=keep_frac, tau_c=0.5, tau_kv=0.75,
+                                       share_of_attn_step=ms / head["ms_per_step"])
+        log(f"symbols_update: {ms:.3f} ms ({extra['symbols_update']['gbps']:.0f} GB/s on Q+K), cached {extra['symbols_update']['cached_frac']:.2f}, "
+            f"kept pairs {keep_frac:.2f}")
+        del Qs, Ks, fl, mk
     extra["dense_equiv_tops"] = head["dense_equiv_tops"]
     extra["sparsity"] = 1.0 - head["keep"]
     extra["plan_ms"] = head["plan_ms"]

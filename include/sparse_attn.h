@@ -138,6 +138,36 @@ int sparse_gemm_o_stream(const void* O, const void* W, const void* bias, const u
                          int block_q, void* hip_stream);
 
 /*
+ * Sparse-symbol generation of an Update step (Section 3.3 "Logical Masks Generation", Equation 1; the
+ * tau_kv and S_q rules of the settings table in the appendix).  From the step's Q and K it writes the
+ * two symbol arrays that sparse_attn_fwd, sparse_gemm_q and sparse_gemm_o read at the following steps.
+ * Per (batch, head), with T = L / block blocks of which the first text_tokens / block are text:
+ *   1. q~, k~ = per-block means of the query / key rows; P~ = row softmax of q~ k~^T / sqrt(D)
+ *   2. C_v = sum over text rows of P~[row, vision block v]; G_v = sum over text columns j of
+ *      softmax over v of P~[vision block v, j]
+ *   3. vision block v is cached iff the ascending cumulative sums (ties by index) of C and of G at v are
+ *      both <= tau_c times the totals; text blocks are never cached; if afterwards the share of the
+ *      head's blocks that still need computation is below s_q, all T blocks are cached
+ *   4. in row i of P~ key block j is skipped iff the ascending cumulative sum at j is <= tau_kv
+ * All arithmetic is fp32; a decision whose deciding sum lies within rounding of its threshold may
+ * differ from an exact evaluation.
+ *   Q, K         device, bf16 [B, H, L, D], 16-byte aligned (read once each)
+ *   cache_flags  device, uint8 [B, H, T], written: 1 = cached
+ *   kv_mask      device, uint8 [B, H, T, ceil(T/8)], written: bit = 1 keeps the pair, first block in
+ *                bit 7 of byte 0, padding bits 0
+ *   text_tokens  number of leading text tokens, a positive multiple of block, < L
+ *   tau_c, tau_kv, s_q  in [0, 1]
+ * Supported: D and block in {64, 128}, T <= 2048.  block is both b_q and b_k (granularity n = 1).
+ * Uses the library's per-stream scratch buffer (grown with hipMalloc on first use).  Errors as for
+ * sparse_attn_fwd.
+ */
+int sparse_symbols_update(const void* Q, const void* K, uint8_t* cache_flags, uint8_t* kv_mask, int B, int H, int L,
+                          int D, int block, int text_tokens, float tau_c, float tau_kv, float s_q);
+int sparse_symbols_update_stream(const void* Q, const void* K, uint8_t* cache_flags, uint8_t* kv_mask, int B, int H,
+                                 int L, int D, int block, int text_tokens, float tau_c, float tau_kv, float s_q,
+                                 void* hip_stream);
+
+/*
  * Live kernel timing for benchmarks.  Between sparse_attn_profile_begin(max_calls) and
  * sparse_attn_profile_end(), each of the first max_calls calls of sparse_attn_fwd /
  * sparse_attn_fwd_stream records three HIP events on its own stream (start, after the symbol

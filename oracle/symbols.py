@@ -71,7 +71,7 @@ def caching_metrics(P, n_t):
     return C, G
 
 
-def update_symbols(Q, K, block, text_tokens, tau_c, tau_kv, s_q=0.0, tie_rel=1e-4):
+def update_symbols(Q, K, block, text_tokens, tau_c, tau_kv, s_q=0.0, tie_rel=1e-5):
     """Steps 1-7 on whole tensors.
 
     Returns a dict with
@@ -81,6 +81,7 @@ def update_symbols(Q, K, block, text_tokens, tau_c, tau_kv, s_q=0.0, tie_rel=1e-
                                       sum (min over the two conditions when cached, max when not); +inf for text
                                       blocks and for heads decided by the degrade rule
       flag_tie     bool  [B,H,T]      a near-tie in the ascending order could move this block's cumulative sums
+      flag_window  fp64  [B,H,T]      ... by at most this much (the block's own share of the metric's total)
       skip_margin  fp64  [B,H,T,T]    tau_kv - CumSum_up (positive = skipped)
       skip_tie     bool  [B,H,T,T]
       own_value    fp64  [B,H,T,T]    P~ itself (how far a near-tie can move a cumulative sum)
@@ -93,6 +94,7 @@ def update_symbols(Q, K, block, text_tokens, tau_c, tau_kv, s_q=0.0, tie_rel=1e-
     flags = np.zeros((B, H, T), dtype=np.uint8)
     flag_margin = np.full((B, H, T), np.inf)
     flag_tie = np.zeros((B, H, T), dtype=bool)
+    flag_window = np.zeros((B, H, T))
     M_s = np.ones((B, H, T, T), dtype=np.uint8)
     skip_margin = np.zeros((B, H, T, T))
     skip_tie = np.zeros((B, H, T, T), dtype=bool)
@@ -109,6 +111,7 @@ def update_symbols(Q, K, block, text_tokens, tau_c, tau_kv, s_q=0.0, tie_rel=1e-
             flags[b, h, n_t:] = cached
             flag_margin[b, h, n_t:] = np.where(cached, np.minimum(dC, dG), np.maximum(np.where(dC < 0, -dC, 0), np.where(dG < 0, -dG, 0)))
             flag_tie[b, h, n_t:] = (gapC < tie_rel) | (gapG < tie_rel)
+            flag_window[b, h, n_t:] = np.maximum(C / csC.max(), G / csG.max())
             if (T - int(cached.sum())) / T < s_q:
                 flags[b, h, :] = 1
                 flag_margin[b, h, :] = np.inf
@@ -118,5 +121,5 @@ def update_symbols(Q, K, block, text_tokens, tau_c, tau_kv, s_q=0.0, tie_rel=1e-
                 skip_margin[b, h, i] = tau_kv - cs
                 skip_tie[b, h, i] = gap < tie_rel
                 M_s[b, h, i] = (cs > tau_kv).astype(np.uint8)
-    return dict(cache_flags=flags, M_s=M_s, flag_margin=flag_margin, flag_tie=flag_tie,
+    return dict(cache_flags=flags, M_s=M_s, flag_margin=flag_margin, flag_tie=flag_tie, flag_window=flag_window,
                 skip_margin=skip_margin, skip_tie=skip_tie, own_value=P)

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     sparse_attn_fwd_timed,
     sparse_gemm_q,
     sparse_gemm_o,
+    sparse_symbols_update,
     sparse_attn_profile_begin,
     sparse_attn_profile_end,
     sparse_attn_pack_mask,

@@ -56,6 +56,11 @@ def load_library():
     lib.sparse_gemm_o.restype = i32
     lib.sparse_gemm_o_stream.argtypes = [vp] * 4 + [i32, vp, vp] + [i32] * 6 + [vp]
     lib.sparse_gemm_o_stream.restype = i32
+    f32 = ctypes.c_float
+    lib.sparse_symbols_update.argtypes = [vp] * 4 + [i32] * 6 + [f32] * 3
+    lib.sparse_symbols_update.restype = i32
+    lib.sparse_symbols_update_stream.argtypes = [vp] * 4 + [i32] * 6 + [f32] * 3 + [vp]
+    lib.sparse_symbols_update_stream.restype = i32
     lib.sparse_attn_profile_begin.argtypes = [i32]
     lib.sparse_attn_profile_begin.restype = i32
     lib.sparse_attn_profile_end.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -164,6 +169,24 @@ def sparse_gemm_o(O, W, bias, cache_flags, select_cached, addend, Out, block_q, 
     if rc != 0:
         _raise(rc)
     return Out
+
+
+def sparse_symbols_update(Q, K, cache_flags, kv_mask, block, text_tokens, tau_c, tau_kv, s_q=0.0, stream=None):
+    """Symbol generation of an Update step on device tensors: Q, K bf16 [B,H,L,D]; writes cache_flags uint8 [B,H,T]
+    (1 = cached) and kv_mask uint8 [B,H,T,ceil(T/8)] (bit = 1 keeps the pair, first block in bit 7), T = L/block."""
+    B, H, L, D = Q.shape
+    if tuple(K.shape) != (B, H, L, D):
+        raise ValueError("Q and K must have the same shape [B,H,L,D]")
+    T = L // block
+    if tuple(cache_flags.shape) != (B, H, T) or tuple(kv_mask.shape) != (B, H, T, (T + 7) // 8):
+        raise ValueError("cache_flags must be [B,H,T] and kv_mask [B,H,T,ceil(T/8)] with T = L/block")
+    rc = load_library().sparse_symbols_update_stream(_dev_ptr(Q, "Q"), _dev_ptr(K, "K"),
+                                                     _dev_ptr(cache_flags, "cache_flags"), _dev_ptr(kv_mask, "kv_mask"),
+                                                     int(B), int(H), int(L), int(D), int(block), int(text_tokens),
+                                                     float(tau_c), float(tau_kv), float(s_q), _stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
+    return cache_flags, kv_mask
 
 
 def sparse_attn_profile_begin(max_calls: int) -> None:

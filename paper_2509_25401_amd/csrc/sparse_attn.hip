@@ -547,7 +547,9 @@ struct Scratch {
 std::mutex g_mu;
 std::map<std::pair<int, void*>, Scratch> g_scratch;
 
-int get_scratch(size_t need, hipStream_t stream, void** out) {
+}  // namespace
+
+int sa_get_scratch(size_t need, hipStream_t stream, void** out) {
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev));
   std::lock_guard<std::mutex> lock(g_mu);
@@ -566,6 +568,8 @@ int get_scratch(size_t need, hipStream_t stream, void** out) {
   *out = sc.ptr;
   return 0;
 }
+
+namespace {
 
 // Optional per-call event recording (sparse_attn_profile_begin/end): three events per call,
 // recorded on the call's stream without any synchronisation.
@@ -611,7 +615,7 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
     return fail(SPARSE_ATTN_ERR_INVALID, "tensor base pointers must be 16-byte aligned");
 
   void* ws = nullptr;
-  if (int rc = get_scratch(workspace_bytes(s), stream, &ws)) return rc;
+  if (int rc = sa_get_scratch(workspace_bytes(s), stream, &ws)) return rc;
   char* base = (char*)ws;
   uint32_t* queues = (uint32_t*)base;
   uint32_t* order = (uint32_t*)(base + 256);

@@ -7,6 +7,11 @@
 // Records a printf-style message for sparse_attn_last_error() on the calling thread and returns `code`.
 int sa_fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 
+// The library's scratch buffer of the current device and `stream`, grown (with a stream synchronisation) to at
+// least `need` bytes.  Every entry point that needs scratch memory shares it: work on one stream runs in
+// order, and no entry point keeps anything in it between calls.
+int sa_get_scratch(size_t need, hipStream_t stream, void** out);
+
 // Direct-to-LDS load: every lane fetches 16 bytes from gbase (wave-uniform) + lane_off, the wave's
 // 1 KiB lands at consecutive LDS addresses starting at the wave-uniform `lds_addr`.  Written as
 // inline assembly so that the compiler does not serialise later LDS reads of the OTHER buffer

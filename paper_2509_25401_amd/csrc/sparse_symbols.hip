@@ -1,0 +1,382 @@
+// Sparse-symbol generation of an Update step (Section 3.3 "Logical Masks Generation", Equation 1, and
+// the tau_kv / S_q rules of the settings table in the appendix) for gfx950.
+//
+// Three kernels, all plain fp32 vector arithmetic:
+//   pool_blocks   mean of the b query rows / key rows of every block: the only pass over Q and K,
+//                 HBM-bound (reads both tensors once, 16 bytes per lane, row-contiguous)
+//   map_rows      one workgroup per 8 rows of the compressed attention map of one head: scores of the
+//                 pooled queries against all pooled keys (scale 1/sqrt(d)), row softmax, then for
+//                 every row the block-skipping rule -- a key block is skipped iff the sum of all row
+//                 entries that come at or before it in ascending order (ties by index) stays <= tau_kv
+//                 -- packed most-significant-bit first into the kv_mask row.  The text rows and text
+//                 columns of the map (all that the caching rule needs) go to scratch memory.
+//   select_blocks one workgroup per head: contribution C_v = sum over text rows of their weight on
+//                 vision block v, guidance G_v = sum over text columns of the softmax, along the vision
+//                 axis, of the vision rows' weights on that column; Equation 1 caches v iff its
+//                 ascending cumulative sums of C and of G both stay <= tau_c times the totals; text
+//                 blocks are never cached; if the share of blocks left to compute drops below S_q,
+//                 every block of the head is cached.
+// The cumulative sums need no sort: entry v adds up every entry that is smaller, or equal with a
+// smaller-or-same index, T^2 compare-and-adds per row with T a few hundred.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "sparse_attn.h"
+#include "sparse_attn_internal.h"
+
+namespace {
+
+constexpr int kMapRows = 8;          // map rows per workgroup (two per wave)
+constexpr int kChunk = 32;           // pooled key rows staged in LDS per step
+constexpr int kCoopTail = 12;        // a last pass with fewer entries than this is done entry by entry
+constexpr int kMaxBlocks = 2048;     // blocks per sequence the LDS arrays are sized for
+
+__device__ __forceinline__ float wave_max(float v) {
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// Block-wide reductions for 256 threads; `red` is 4 floats of LDS.  Every thread gets the result.
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();
+  if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// pooled[which][block][d] = mean over the block's rows; grid (n_blocks, 2), which = 0 for Q, 1 for K
+template <int D>
+__global__ void __launch_bounds__(256) pool_blocks(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+                                                   float* __restrict__ pooled, int block, long long n_blocks) {
+  constexpr int TPR = D / 8;          // threads per row, 8 bf16 = 16 bytes each
+  constexpr int RPP = 256 / TPR;      // rows per pass
+  __shared__ float part[RPP][D];
+  const uint16_t* src = (blockIdx.y ? K : Q) + (size_t)blockIdx.x * block * D;
+  const int c = threadIdx.x % TPR, r0 = threadIdx.x / TPR;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int r = r0; r < block; r += RPP) {
+    const uint4 v = *(const uint4*)(src + (size_t)r * D + c * 8);
+    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc[2 * e] += __uint_as_float(w[e] << 16);
+      acc[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[r0][c * 8 + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < D) {
+    float s = 0.f;
+    for (int r = 0; r < RPP; ++r) s += part[r][threadIdx.x];
+    pooled[((size_t)blockIdx.y * n_blocks + blockIdx.x) * D + threadIdx.x] = s * (1.0f / (float)block);
+  }
+}
+
+// Entry t of a row's ascending cumulative sum: every entry that is smaller, or equal with index <= t.
+// Entries before the 64 that this pass of the wave owns have a smaller index than all of them (so "<="
+// decides), entries after them a larger one ("<" decides); only the 64 in between need the index.
+// `pr` is padded to a multiple of 4 entries with +inf, which no comparison ever selects.
+// Two rows (pa, pb) are walked together so that their independent compare / select / add chains interleave.
+__device__ __forceinline__ void cumsum_up_at2(const float* pa, const float* pb, int T_pad, int j0, int j, float aj,
+                                              float bj, float& cs_a, float& cs_b) {
+  float ca = 0.f, cb = 0.f;
+  int k = 0;
+  for (; k < j0; k += 4) {
+    const float4 a = *(const float4*)&pa[k], b = *(const float4*)&pb[k];
+    ca += a.x <= aj ? a.x : 0.f;
+    cb += b.x <= bj ? b.x : 0.f;
+    ca += a.y <= aj ? a.y : 0.f;
+    cb += b.y <= bj ? b.y : 0.f;
+    ca += a.z <= aj ? a.z : 0.f;
+    cb += b.z <= bj ? b.z : 0.f;
+    ca += a.w <= aj ? a.w : 0.f;
+    cb += b.w <= bj ? b.w : 0.f;
+  }
+  const int mid_end = min(j0 + 64, T_pad);
+  for (; k < mid_end; ++k) {
+    const float a = pa[k], b = pb[k];
+    const bool first = k <= j;
+    ca += ((a < aj) | ((a == aj) & first)) ? a : 0.f;      // bitwise on purpose: no branches
+    cb += ((b < bj) | ((b == bj) & first)) ? b : 0.f;
+  }
+  for (; k < T_pad; k += 4) {
+    const float4 a = *(const float4*)&pa[k], b = *(const float4*)&pb[k];
+    ca += a.x < aj ? a.x : 0.f;
+    cb += b.x < bj ? b.x : 0.f;
+    ca += a.y < aj ? a.y : 0.f;
+    cb += b.y < bj ? b.y : 0.f;
+    ca += a.z < aj ? a.z : 0.f;
+    cb += b.z < bj ? b.z : 0.f;
+    ca += a.w < aj ? a.w : 0.f;
+    cb += b.w < bj ? b.w : 0.f;
+  }
+  cs_a = ca;
+  cs_b = cb;
+}
+
+// Dynamic LDS: pooled query rows [kMapRows][D], one stage of pooled key rows [kChunk][D + 4] (padded so
+// that 16 lanes reading 16 bytes of 16 different rows hit 64 different banks), map rows [kMapRows][T_pad].
+template <int D>
+__global__ void __launch_bounds__(256) map_rows(const float* __restrict__ pooled, long long n_blocks, int T, int T_pad,
+                                                int n_t, int row_bytes, float scale, float tau_kv,
+                                                uint8_t* __restrict__ kv_mask, float* __restrict__ text_rows,
+                                                float* __restrict__ text_cols) {
+  extern __shared__ float lds[];
+  constexpr int KS = D + 4;
+  float* q = lds;
+  float* kst = q + kMapRows * D;
+  float* p = kst + kChunk * KS;
+  const int tid = threadIdx.x;
+  const int groups = (T + kMapRows - 1) / kMapRows;
+  const int bh = blockIdx.x / groups, i0 = (blockIdx.x % groups) * kMapRows;
+  const float* qt = pooled + (size_t)bh * T * D;
+  const float* kt = pooled + ((size_t)n_blocks + (size_t)bh * T) * D;
+  for (int e = tid; e < kMapRows * D; e += 256) {
+    const int r = e / D, i = min(i0 + r, T - 1);
+    q[e] = qt[(size_t)i * D + e % D];
+  }
+  for (int e = tid; e < kMapRows * (T_pad - T); e += 256) p[(e / (T_pad - T)) * T_pad + T + e % (T_pad - T)] = INFINITY;
+
+  // scores: keys come through LDS kChunk at a time (coalesced 16-byte reads of the pooled keys); thread
+  // (key tid % kChunk, row tid / kChunk) then takes one dot product
+  static_assert(256 / kChunk == kMapRows, "one thread per (staged key, row)");
+  const int jj = tid % kChunk, r = tid / kChunk;
+  for (int j0 = 0; j0 < T; j0 += kChunk) {
+    __syncthreads();
+    const int nk = min(kChunk, T - j0);
+    for (int e = tid; e < nk * (D / 4); e += 256) {
+      const int kr = e / (D / 4), c = e % (D / 4);
+      *(float4*)&kst[kr * KS + 4 * c] = *(const float4*)&kt[(size_t)(j0 + kr) * D + 4 * c];
+    }
+    __syncthreads();
+    if (jj < nk) {
+      const float4* kr = (const float4*)(kst + jj * KS);
+      const float4* qr = (const float4*)(q + r * D);
+      float s0 = 0.f, s1 = 0.f;                         // two partial sums: even and odd 16-byte groups
+#pragma unroll 8
+      for (int c = 0; c < D / 4; c += 2) {
+        const float4 k0 = kr[c], a0 = qr[c], k1 = kr[c + 1], a1 = qr[c + 1];
+        s0 += k0.x * a0.x + k0.y * a0.y + k0.z * a0.z + k0.w * a0.w;
+        s1 += k1.x * a1.x + k1.y * a1.y + k1.z * a1.z + k1.w * a1.w;
+      }
+      p[r * T_pad + j0 + jj] = (s0 + s1) * scale;
+    }
+  }
+  __syncthreads();
+
+  // each wave owns two rows from here on; all waves run the same loops (bounds depend on T only)
+  const int w = tid / 64, lane = tid % 64;
+  for (int rr = 0; rr < 2; ++rr) {
+    const int i = i0 + 2 * w + rr;
+    float* pr = p + (2 * w + rr) * T_pad;
+    float m = -INFINITY;
+    for (int j = lane; j < T; j += 64) m = fmaxf(m, pr[j]);
+    m = wave_max(m);
+    float sum = 0.f;
+    for (int j = lane; j < T; j += 64) {
+      const float e = expf(pr[j] - m);
+      pr[j] = e;
+      sum += e;
+    }
+    sum = wave_sum(sum);
+    for (int j = lane; j < T; j += 64) {
+      const float v = pr[j] / sum;
+      pr[j] = v;
+      if (i < n_t) text_rows[((size_t)bh * n_t + i) * T + j] = v;        // i < n_t < T
+      if (j < n_t && i < T) text_cols[((size_t)bh * T + i) * n_t + j] = v;
+    }
+  }
+  __syncthreads();
+
+  const float* pa = p + (2 * w) * T_pad;
+  const float* pb = pa + T_pad;
+  const int ia = i0 + 2 * w, ib = ia + 1;
+  for (int j0 = 0; j0 < T; j0 += 64) {
+    unsigned long long kept_a = 0, kept_b = 0;              // bit l = key block j0 + l is kept
+    const int rem = T - j0;
+    if (rem >= kCoopTail) {
+      // every lane owns one entry of each row and walks over all others
+      const int j = j0 + lane;
+      const float aj = j < T ? pa[j] : 0.f, bj = j < T ? pb[j] : 0.f;
+      float cs_a, cs_b;
+      cumsum_up_at2(pa, pb, T_pad, j0, j, aj, bj, cs_a, cs_b);
+      kept_a = __ballot(j < T && cs_a > tau_kv);
+      kept_b = __ballot(j < T && cs_b > tau_kv);
+    } else {
+      // a short ragged tail: the whole wave works on one entry at a time instead of idling most lanes
+      for (int t = 0; t < rem; ++t) {
+        const int j = j0 + t;
+        const float aj = pa[j], bj = pb[j];
+        float part_a = 0.f, part_b = 0.f;
+        for (int k = lane; k < T; k += 64) {
+          const float a = pa[k], b = pb[k];
+          const bool first = k <= j;
+          part_a += ((a < aj) | ((a == aj) & first)) ? a : 0.f;
+          part_b += ((b < bj) | ((b == bj) & first)) ? b : 0.f;
+        }
+        if (wave_sum(part_a) > tau_kv) kept_a |= 1ull << t;   // the butterfly leaves the same sum in every lane
+        if (wave_sum(part_b) > tau_kv) kept_b |= 1ull << t;
+      }
+    }
+    // lanes 0-7 write the bytes of row a, lanes 8-15 those of row b; first block of a byte = bit 7
+    const int byte = j0 / 8 + (lane & 7);
+    const int i = lane < 8 ? ia : ib;
+    if (lane < 16 && i < T && byte < row_bytes) {
+      const unsigned long long kept = lane < 8 ? kept_a : kept_b;
+      const unsigned bits = (unsigned)(kept >> (8 * (lane & 7))) & 0xffu;
+      kv_mask[((size_t)bh * T + i) * row_bytes + byte] = (uint8_t)(__brev(bits) >> 24);
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) select_blocks(const float* __restrict__ text_rows,
+                                                     const float* __restrict__ text_cols, int T, int n_t, float tau_c,
+                                                     float s_q, uint8_t* __restrict__ cache_flags) {
+  __shared__ float C[kMaxBlocks], G[kMaxBlocks];
+  __shared__ float red[4];
+  const int bh = blockIdx.x, Tv = T - n_t, tid = threadIdx.x;
+  const float* tr = text_rows + (size_t)bh * n_t * T;
+  const float* tc = text_cols + (size_t)bh * T * n_t;
+  for (int v = tid; v < Tv; v += 256) {
+    float c = 0.f;
+    for (int j = 0; j < n_t; ++j) c += tr[(size_t)j * T + n_t + v];
+    C[v] = c;
+    G[v] = 0.f;
+  }
+  for (int j = 0; j < n_t; ++j) {
+    float m = -INFINITY;
+    for (int v = tid; v < Tv; v += 256) m = fmaxf(m, tc[(size_t)(n_t + v) * n_t + j]);
+    m = block_max(m, red);
+    float s = 0.f;
+    for (int v = tid; v < Tv; v += 256) s += expf(tc[(size_t)(n_t + v) * n_t + j] - m);
+    s = block_sum(s, red);
+    for (int v = tid; v < Tv; v += 256) G[v] += expf(tc[(size_t)(n_t + v) * n_t + j] - m) / s;   // v belongs to one thread
+  }
+  __syncthreads();
+  // totals in index order: what the ascending sum of the largest entry adds up to as well
+  float tot_c = 0.f, tot_g = 0.f;
+  for (int u = 0; u < Tv; ++u) {
+    tot_c += C[u];
+    tot_g += G[u];
+  }
+  int n_cached = 0;
+  unsigned mine = 0;                               // decisions of this thread's blocks, bit n = block tid + 256 n
+  for (int v = tid, n = 0; v < Tv; v += 256, ++n) {
+    const float cv = C[v], gv = G[v];
+    float cs_c = 0.f, cs_g = 0.f;
+    for (int u = 0; u < Tv; ++u) {
+      const float cu = C[u], gu = G[u];
+      cs_c += ((cu < cv) | ((cu == cv) & (u <= v))) ? cu : 0.f;      // bitwise on purpose: no branches
+      cs_g += ((gu < gv) | ((gu == gv) & (u <= v))) ? gu : 0.f;
+    }
+    const bool cached = cs_c <= tau_c * tot_c && cs_g <= tau_c * tot_g;
+    mine |= (cached ? 1u : 0u) << n;
+    n_cached += cached ? 1 : 0;
+  }
+  const float total_cached = block_sum((float)n_cached, red);    // exact: counts stay far below 2^24
+  const bool degrade = ((float)T - total_cached) / (float)T < s_q;
+  uint8_t* out = cache_flags + (size_t)bh * T;
+  for (int b = tid; b < n_t; b += 256) out[b] = degrade ? 1 : 0;
+  for (int v = tid, n = 0; v < Tv; v += 256, ++n) out[n_t + v] = (degrade || ((mine >> n) & 1u)) ? 1 : 0;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+#define HIP_TRY(expr)                                                                                \
+  do {                                                                                               \
+    hipError_t e_ = (expr);                                                                          \
+    if (e_ != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int sparse_symbols_update_stream(const void* Q, const void* K, uint8_t* cache_flags, uint8_t* kv_mask, int B, int H,
+                                 int L, int D, int block, int text_tokens, float tau_c, float tau_kv, float s_q,
+                                 void* hip_stream) {
+  if (B <= 0 || H <= 0 || L <= 0 || D <= 0 || block <= 0)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: sizes must be positive (B=%d H=%d L=%d D=%d block=%d)", B, H, L, D,
+                   block);
+  if ((D != 64 && D != 128) || (block != 64 && block != 128))
+    return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: D and block must be 64 or 128 (got %d, %d)", D, block);
+  if (L % block || text_tokens % block)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: L=%d and text_tokens=%d must be multiples of block=%d", L,
+                   text_tokens, block);
+  if (text_tokens <= 0 || text_tokens >= L)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: text_tokens=%d must leave text and vision blocks (L=%d)",
+                   text_tokens, L);
+  const int T = L / block, n_t = text_tokens / block;
+  if (T > kMaxBlocks) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: %d blocks exceed %d", T, kMaxBlocks);
+  if (T - n_t > 256 * 32) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: too many vision blocks (%d)", T - n_t);
+  if (!(tau_c >= 0.f && tau_c <= 1.f) || !(tau_kv >= 0.f && tau_kv <= 1.f) || !(s_q >= 0.f && s_q <= 1.f))
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: tau_c, tau_kv and s_q must lie in [0, 1] (got %g, %g, %g)",
+                   (double)tau_c, (double)tau_kv, (double)s_q);
+  const long long n_blocks = (long long)B * H * T;
+  if (n_blocks > 0x3fffffffLL) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: too many blocks (%lld)", n_blocks);
+  if (!Q || !K || !cache_flags || !kv_mask)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: Q, K, cache_flags and kv_mask must not be NULL");
+  if (((uintptr_t)Q | (uintptr_t)K) & 15) return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: Q and K must be 16-byte aligned");
+
+  hipStream_t stream = (hipStream_t)hip_stream;
+  const size_t pooled_b = align256((size_t)2 * n_blocks * D * 4);
+  const size_t slice_b = align256((size_t)B * H * n_t * T * 4);
+  void* ws = nullptr;
+  if (int rc = sa_get_scratch(pooled_b + 2 * slice_b, stream, &ws)) return rc;
+  float* pooled = (float*)ws;
+  float* text_rows = (float*)((char*)ws + pooled_b);
+  float* text_cols = (float*)((char*)ws + pooled_b + slice_b);
+
+  const int row_bytes = (T + 7) / 8;
+  const float scale = (float)(1.0 / sqrt((double)D));
+  const int groups = (T + kMapRows - 1) / kMapRows;
+  const int T_pad = (T + 3) & ~3;
+  const size_t map_lds = ((size_t)kMapRows * D + (size_t)kChunk * (D + 4) + (size_t)kMapRows * T_pad) * 4;
+  static bool attr_set = false;
+  if (!attr_set) {
+    constexpr int kMaxLds = (kMapRows * 128 + kChunk * 132 + kMapRows * kMaxBlocks) * 4;
+    HIP_TRY(hipFuncSetAttribute((const void*)map_rows<128>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds));
+    HIP_TRY(hipFuncSetAttribute((const void*)map_rows<64>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds));
+    attr_set = true;
+  }
+  if (D == 128) {
+    hipLaunchKernelGGL(pool_blocks<128>, dim3((unsigned)n_blocks, 2), dim3(256), 0, stream, (const uint16_t*)Q,
+                       (const uint16_t*)K, pooled, block, n_blocks);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(map_rows<128>, dim3((unsigned)(B * H * groups)), dim3(256), map_lds, stream, pooled, n_blocks, T, T_pad, n_t,
+                       row_bytes, scale, tau_kv, kv_mask, text_rows, text_cols);
+  } else {
+    hipLaunchKernelGGL(pool_blocks<64>, dim3((unsigned)n_blocks, 2), dim3(256), 0, stream, (const uint16_t*)Q,
+                       (const uint16_t*)K, pooled, block, n_blocks);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(map_rows<64>, dim3((unsigned)(B * H * groups)), dim3(256), map_lds, stream, pooled, n_blocks, T, T_pad, n_t,
+                       row_bytes, scale, tau_kv, kv_mask, text_rows, text_cols);
+  }
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(select_blocks, dim3((unsigned)(B * H)), dim3(256), 0, stream, text_rows, text_cols, T, n_t, tau_c,
+                     s_q, cache_flags);
+  HIP_TRY(hipGetLastError());
+  return 0;
+}
+
+int sparse_symbols_update(const void* Q, const void* K, uint8_t* cache_flags, uint8_t* kv_mask, int B, int H, int L,
+                          int D, int block, int text_tokens, float tau_c, float tau_kv, float s_q) {
+  return sparse_symbols_update_stream(Q, K, cache_flags, kv_mask, B, H, L, D, block, text_tokens, tau_c, tau_kv, s_q,
+                                      nullptr);
+}
+
+}  // extern "C"

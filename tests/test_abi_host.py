@@ -22,14 +22,14 @@ def _declared_functions():
             continue
         text = open(os.path.join(inc, fn)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names += re.findall(r"\b(sparse_(?:attn|gemm)_\w+)\s*\(", text)
+        names += re.findall(r"\b(sparse_(?:attn|gemm|symbols)_\w+)\s*\(", text)
     return sorted(set(names))
 
 
 def test_library_exports_every_declared_symbol():
     lib = pkg.load_library()
     names = _declared_functions()
-    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and "sparse_gemm_o" in names and len(names) >= 12
+    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and "sparse_gemm_o" in names and "sparse_symbols_update" in names and len(names) >= 14
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
     assert pkg.sparse_attn_version() >= 100
@@ -131,4 +131,24 @@ def _gemm_o(B=1, H=2, L=128, D=128, C_out=128, bq=128, sel=0, O=FAKE, W=ctypes.c
 ])
 def test_gemm_o_argument_validation_precedes_any_device_work(kw, code):
     assert _gemm_o(**kw) == code
+    assert pkg.sparse_attn_last_error() != ""
+
+
+def _symbols(B=1, H=1, L=512, D=128, blk=128, text=128, tau_c=0.5, tau_kv=0.1, s_q=0.0, Q=FAKE,
+             K=ctypes.c_void_p(0x20000000), flags=ctypes.c_void_p(0x30000000), mask=ctypes.c_void_p(0x40000000)):
+    return pkg.load_library().sparse_symbols_update(Q, K, flags, mask, B, H, L, D, blk, text, tau_c, tau_kv, s_q)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(B=0), -1), (dict(H=0), -1), (dict(L=0), -1), (dict(D=0), -1), (dict(blk=0), -1),
+    (dict(L=576), -1), (dict(text=64), -1),                 # not multiples of the block
+    (dict(text=0), -1), (dict(text=512), -1),               # no text blocks / no vision blocks
+    (dict(D=96), -2), (dict(blk=32), -2),
+    (dict(L=128 * 2049, text=128), -2),                      # more blocks than the kernels are sized for
+    (dict(tau_c=-0.1), -1), (dict(tau_c=1.5), -1), (dict(tau_kv=float("nan")), -1), (dict(s_q=2.0), -1),
+    (dict(Q=None), -1), (dict(K=None), -1), (dict(flags=None), -1), (dict(mask=None), -1),
+    (dict(Q=ctypes.c_void_p(0x10004)), -1),
+])
+def test_symbols_argument_validation_precedes_any_device_work(kw, code):
+    assert _symbols(**kw) == code
     assert pkg.sparse_attn_last_error() != ""

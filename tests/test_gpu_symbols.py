@@ -1,0 +1,138 @@
+"""GPU parity of the symbol generation (sparse_symbols_update) against the fp64 oracle.
+
+The kernels decide in fp32, the oracle in fp64.  A yes/no decision is compared wherever the oracle's deciding
+quantity is further from its threshold than fp32 rounding can move it (and than a near-tie in the ascending order
+could move it); the remaining, undecidable entries must be rare."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_25401_amd as pkg
+from paper_2509_25401_amd import synth
+from gpu_utils import dev, up_bf16, down_bits, check_against_oracle
+
+pytestmark = pytest.mark.gpu
+
+EPS_FLAG = 1e-4     # relative to the metric's total
+EPS_SKIP = 2e-5     # absolute: rows of the map sum to one
+
+
+def f32(x):
+    return float(np.float32(x))
+
+
+def run_gpu(Q, K, block, text, tau_c, tau_kv, s_q=0.0):
+    B, H, L, D = Q.shape
+    T = L // block
+    flags = torch.full((B, H, T), 0xAA, dtype=torch.uint8, device=dev())
+    mask = torch.full((B, H, T, (T + 7) // 8), 0xAA, dtype=torch.uint8, device=dev())
+    pkg.sparse_symbols_update(up_bf16(Q), up_bf16(K), flags, mask, block, text, tau_c, tau_kv, s_q)
+    torch.cuda.synchronize()
+    return flags.cpu().numpy(), mask.cpu().numpy()
+
+
+def compare(ref, flags, mask, T, label, max_ambiguous=0.02):
+    bits = oracle.unpack_symbols(mask, T)
+    # padding bits of the last byte are zero
+    if T % 8:
+        assert (mask[..., -1] & ((1 << (8 - T % 8)) - 1) == 0).all(), f"{label}: padding bits set"
+    assert set(np.unique(flags)) <= {0, 1}
+    robust_f = ref["flag_margin"] > EPS_FLAG + np.where(ref["flag_tie"], 2 * ref["flag_window"], 0.0)
+    robust_s = np.abs(ref["skip_margin"]) > EPS_SKIP + np.where(ref["skip_tie"], 2 * ref["own_value"], 0.0)
+    bad_f = (flags != ref["cache_flags"]) & robust_f
+    bad_s = (bits != ref["M_s"]) & robust_s
+    print(f"[symbols] {label}: cached {ref['cache_flags'].mean():.3f} kept {ref['M_s'].mean():.3f} "
+          f"undecidable flags {(~robust_f).mean():.4f} pairs {(~robust_s).mean():.5f} "
+          f"raw mismatches flags {(flags != ref['cache_flags']).sum()} pairs {(bits != ref['M_s']).sum()}", flush=True)
+    assert not bad_f.any(), f"{label}: {bad_f.sum()} cache flags differ from the oracle beyond rounding"
+    assert not bad_s.any(), f"{label}: {bad_s.sum()} mask bits differ from the oracle beyond rounding"
+    assert (~robust_f).mean() <= max_ambiguous and (~robust_s).mean() <= max_ambiguous
+    return bits
+
+
+@pytest.mark.parametrize("B,H,L,D,block,text,tau_c,tau_kv", [
+    (1, 2, 1024, 128, 128, 256, 0.5, 0.1),        # 8 blocks, 2 text
+    (2, 3, 2560, 128, 128, 128, 0.3, 0.2),        # 20 blocks, 1 text block, row groups with a ragged tail
+    (1, 2, 4160, 64, 64, 192, 0.6, 0.05),         # 65 blocks (more than one lane pass), D = 64, 3 text blocks
+    (1, 2, 8320, 128, 64, 256, 0.4, 0.3),         # 130 blocks at block 64, D = 128
+    (1, 1, 33280, 64, 128, 512, 0.5, 0.15),       # 260 blocks (more than 256: two thread passes), 4 text blocks
+])
+def test_symbols_match_oracle(B, H, L, D, block, text, tau_c, tau_kv):
+    tau_c, tau_kv = f32(tau_c), f32(tau_kv)
+    Q, K = synth.structured_qk(synth.BASE_SEED + L + D, B, H, L, D, block)
+    ref = oracle.update_symbols(Q, K, block, text, tau_c, tau_kv)
+    flags, mask = run_gpu(Q, K, block, text, tau_c, tau_kv)
+    compare(ref, flags, mask, L // block, f"L{L}_D{D}_b{block}")
+    assert (flags[..., : text // block] == 0).all()
+
+
+def test_threshold_extremes_and_degrade_rule():
+    B, H, L, D, block, text = 1, 2, 2048, 128, 128, 256
+    Q, K = synth.structured_qk(synth.BASE_SEED + 7, B, H, L, D, block)
+    T, nt = L // block, text // block
+    flags, mask = run_gpu(Q, K, block, text, 0.0, 0.0)
+    assert flags.sum() == 0 and (oracle.unpack_symbols(mask, T) == 1).all()
+    flags, mask = run_gpu(Q, K, block, text, 1.0, 0.0)
+    assert (flags[..., nt:] == 1).all() and (flags[..., :nt] == 0).all()
+    # degrade: with tau_c = 1 only the 2 text blocks of 16 need computation (0.125)
+    flags, _ = run_gpu(Q, K, block, text, 1.0, 0.0, s_q=0.25)
+    assert (flags == 1).all()
+    flags, _ = run_gpu(Q, K, block, text, 1.0, 0.0, s_q=0.0625)
+    assert (flags[..., :nt] == 0).all()
+    # tau_kv = 1 skips every block whose cumulative sum stays <= 1: everything except possibly the largest
+    _, mask = run_gpu(Q, K, block, text, 0.0, 1.0)
+    assert oracle.unpack_symbols(mask, T).sum(axis=-1).max() <= 1
+
+
+def test_uniform_map_closed_form_and_repeatability():
+    """Q = 0: all entries tie, ties go by index, so exactly the first floor(tau * count) entries are taken."""
+    B, H, L, D, block, text = 1, 2, 2560, 128, 128, 512       # 20 blocks, 4 text, 16 vision
+    _, K = synth.structured_qk(synth.BASE_SEED + 8, B, H, L, D, block)
+    Q = np.zeros_like(K)
+    flags, mask = run_gpu(Q, K, block, text, f32(0.33), f32(0.27))
+    assert (flags[:, :, :4] == 0).all() and (flags[:, :, 4:9] == 1).all() and (flags[:, :, 9:] == 0).all()
+    bits = oracle.unpack_symbols(mask, 20)
+    assert (bits[..., :5] == 0).all() and (bits[..., 5:] == 1).all()
+    flags2, mask2 = run_gpu(Q, K, block, text, f32(0.33), f32(0.27))
+    assert (flags2 == flags).all() and (mask2 == mask).all()
+
+
+def test_video_size_symbols_and_the_attention_they_drive():
+    """Full sequence length of the video workload (258 blocks, 2 of them text), 4 heads; then the symbols the GPU
+    wrote drive the attention kernel, checked against the oracle run on the ORACLE's symbols over the rows where
+    both sets of symbols agree."""
+    B, H, L, D, block, text = 1, 4, 33024, 128, 128, 256
+    tau_c, tau_kv = f32(0.5), f32(0.2)
+    Q, K = synth.structured_qk(synth.BASE_SEED + 9, B, H, L, D, block)
+    V = synth.normal_bf16(np.random.default_rng(synth.BASE_SEED + 10), (B, H, L, D))
+    Oc = synth.normal_bf16(np.random.default_rng(synth.BASE_SEED + 11), (B, H, L, D))
+    ref = oracle.update_symbols(Q, K, block, text, tau_c, tau_kv)
+    T = L // block
+    dQ, dK, dV, dOc = up_bf16(Q), up_bf16(K), up_bf16(V), up_bf16(Oc)
+    flags = torch.zeros((B, H, T), dtype=torch.uint8, device=dev())
+    mask = torch.zeros((B, H, T, (T + 7) // 8), dtype=torch.uint8, device=dev())
+    pkg.sparse_symbols_update(dQ, dK, flags, mask, block, text, tau_c, tau_kv)
+    O = torch.zeros_like(dQ)
+    pkg.sparse_attn_fwd(dQ, dK, dV, flags, mask, dOc, O, block, block)
+    torch.cuda.synchronize()
+    bits = compare(ref, flags.cpu().numpy(), mask.cpu().numpy(), T, "video33k")
+    same = (flags.cpu().numpy() == ref["cache_flags"]) & (bits == ref["M_s"]).all(axis=-1)      # [B,H,T]
+    assert same.mean() > 0.95
+    rng = np.random.default_rng(5)
+    cand = np.argwhere(same)
+    items = cand[rng.choice(len(cand), size=24, replace=False)]
+    flat = np.array([(b * H + h) * T + i for b, h, i in items], dtype=np.int64)
+    got = down_bits(O)
+    ref_o, ref_bits = oracle.sparse_attention_blocks(Q, K, V, ref["cache_flags"], oracle.pack_symbols(ref["M_s"]), Oc,
+                                                     block, block, flat)
+    n_cached = 0
+    for n, (b, h, i) in enumerate(items):
+        rows = slice(i * block, (i + 1) * block)
+        if ref["cache_flags"][b, h, i]:
+            assert (got[b, h, rows] == Oc[b, h, rows]).all()
+            n_cached += 1
+        else:
+            err = np.abs(synth.bf16_bits_to_f32(got[b, h, rows]).astype(np.float64) - ref_o[n])
+            assert err.max() <= 1e-2 and err.mean() <= 1e-3
+    print(f"[symbols] video33k pipeline: {len(items)} sampled blocks ({n_cached} cached) match the oracle", flush=True)
