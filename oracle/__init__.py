@@ -6,7 +6,8 @@ Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
 package; the product package never does, and the two share no code.
 
 `gemm_q` and `gemm_o` are the same kind of restatement for the sparse query and output projections
-(Section 3.5), `update_symbols` for the symbol generation of an Update step (Section 3.3, Equation 1).
+(Section 3.5), `update_symbols` for the symbol generation of an Update step (Section 3.3, Equation 1),
+`op_reuse` for the Taylor-series forecast of cached features.
 
 Parity status: every function here is pinned by the CPU test-suite (printed packing
 example, textbook dense attention, closed forms, brute force).  Numerical parity with
@@ -14,6 +15,7 @@ the authors' own kernel is unpinned: the paper prints no attention outputs.
 """
 from .gemm_q import gemm_q, computed_flops as gemm_q_flops  # noqa: F401
 from .gemm_o import gemm_o, reduced_heads as gemm_o_segments, speedup_model as gemm_o_speedup_model  # noqa: F401
+from .op_reuse import taylor_coefficients, op_reuse, attention_with_forecast  # noqa: F401
 from .symbols import update_symbols, compressed_map, caching_metrics  # noqa: F401
 from .reference import (  # noqa: F401
     pack_symbols,
