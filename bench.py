@@ -143,7 +143,19 @@ def main():
                                 cached_blocks=ncached, speedup_vs_dense=dense["ms_per_step"] / r4["ms_per_step"],
                                 ideal_speedup=1.0 / r4["keep"],
                                 copy_bytes=2 * ncached * w.block_q * w.D * 2)
-        del Oc
+        # same workload with OP_reuse = first-order Taylor forecast in the cache branch (two stored terms)
+        fl4, mk4 = up_u8(w4.cache_flags), up_u8(pkg.sparse_attn_pack_mask(w4.M_s))
+        coef = pkg.sparse_taylor_coefficients(1, 2.0)
+        for _ in range(2):
+            pkg.sparse_attn_fwd_forecast(Q, K, V, fl4, mk4, [Oc, V], coef, O, w.block_q, w.block_k)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(few):
+            pkg.sparse_attn_fwd_forecast(Q, K, V, fl4, mk4, [Oc, V], coef, O, w.block_q, w.block_k)
+        torch.cuda.synchronize()
+        extra["config4"]["ms_per_step_taylor_order1"] = (time.perf_counter() - t) / few * 1e3
+        log(f"config4 with first-order forecast in the cache branch: {extra['config4']['ms_per_step_taylor_order1']:.3f} ms/step")
+        del Oc, fl4, mk4
         Q.copy_(up_bf16(w.Q)); K.copy_(up_bf16(w.K)); V.copy_(up_bf16(w.V))
     if not args.no_extras:
         # the step before attention (GEMM-Q, Section 3.5): 3072 channels -> 24 heads x 128, flags skip tiles
@@ -203,7 +215,22 @@ def main():
             log(f"gemm_o stage 2 cached {sfrac:.2f}: {ms:.3f} ms, {go[-1]['speedup_vs_dense']:.2f}x; over N=6 steps "
                 f"{go[-1]['aggregated_speedup_N6']:.2f}x (model {go[-1]['model_speedup_N6']:.2f}x)")
         extra["gemm_o"] = go
-        del Wp, Wo, Bc, Yo
+        # OP_reuse(B_c) as the stand-alone element-wise kernel: Yo = 1 * B_c + 2 * B_c' (first-order forecast)
+        Bd = torch.randn((w.B, w.L, C), device=dev, generator=g).to(torch.bfloat16)
+        for _ in range(2):
+            pkg.sparse_op_reuse([Bc, Bd], [1.0, 2.0], Yo)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            pkg.sparse_op_reuse([Bc, Bd], [1.0, 2.0], Yo)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        extra["op_reuse"] = dict(n_terms=2, elems=Yo.numel(), ms=ms, hbm_bytes=3 * Yo.numel() * 2,
+                                 gbps=3 * Yo.numel() * 2 / ms / 1e6, frac_of_hbm_peak=3 * Yo.numel() * 2 / ms / 1e6 / 8000.0)
+        log(f"op_reuse 2 terms on [L, {C}]: {ms:.3f} ms, {extra['op_reuse']['gbps']:.0f} GB/s")
+        del Wp, Wo, Bc, Yo, Bd
         # the symbol generation of an Update step (Section 3.3): reads Q and K once, writes both symbol arrays
         text_tokens = 2 * w.block_q
         fl = torch.empty((w.B, w.H, w.Tq), dtype=torch.uint8, device=dev)

@@ -138,6 +138,38 @@ int sparse_gemm_o_stream(const void* O, const void* W, const void* bias, const u
                          int block_q, void* hip_stream);
 
 /*
+ * OP_reuse as a Taylor-series forecast (Section 3.3: cached blocks are forecast from stored features and their
+ * derivatives; Section 3.4: the cache-then-reuse branch is an element-wise sum of products fused into the
+ * attention kernel, or a separate element-wise kernel; Section 3.5: the same operation transforms the cached
+ * bias B_c).  The operation is
+ *     OP_reuse(terms) = sum over d = 0..n_terms-1 of coef[d] * terms[d]
+ * with terms[0] the stored feature, terms[d] its d-th derivative per step and coef[d] = k^d / d! for a forecast
+ * k steps after the features were stored (sparse_taylor_coefficients writes these weights; estimating the
+ * derivatives is the caller's business).  bf16 terms, fp32 sum in term order, one rounding to bf16 (nearest
+ * even).  n_terms is 1..4; n_terms = 1 with coef[0] = 1 is the bit-exact copy of sparse_attn_fwd.
+ *
+ * sparse_attn_fwd_forecast: Algorithm 1 with this OP_reuse in its cache branch.  All arguments as for
+ * sparse_attn_fwd_stream, except
+ *   O_terms  HOST array of n_terms DEVICE pointers, each bf16 [B,H,L,D], 16-byte aligned, none overlapping O
+ *   coef     HOST array of n_terms finite weights
+ * Only the blocks whose flag is set are read from the terms.
+ *
+ * sparse_op_reuse: the element-wise kernel on flat arrays of n_elems bf16 values (a positive multiple of 8).
+ *   terms    HOST array of n_terms DEVICE pointers, 16-byte aligned; a term may be `out` itself (in place)
+ *   out      DEVICE, 16-byte aligned, written everywhere
+ * Typical use: Out = OP_reuse(B_c terms), then sparse_gemm_o(..., addend = Out, Out) adds the computed heads.
+ *
+ * Errors as for sparse_attn_fwd.  Neither call allocates beyond what sparse_attn_fwd does.
+ */
+int sparse_attn_fwd_forecast(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
+                             const uint8_t* kv_mask, const void* const* O_terms, const float* coef, int n_terms, void* O,
+                             int B, int H, int L, int D, int block_q, int block_k, void* hip_stream);
+int sparse_op_reuse(const void* const* terms, const float* coef, int n_terms, void* out, unsigned long long n_elems,
+                    void* hip_stream);
+/* coef[d] = steps^d / d! for d = 0..order (host arrays; coef holds order + 1 floats). */
+void sparse_taylor_coefficients(int order, float steps, float* coef);
+
+/*
  * Sparse-symbol generation of an Update step (Section 3.3 "Logical Masks Generation", Equation 1; the
  * tau_kv and S_q rules of the settings table in the appendix).  From the step's Q and K it writes the
  * two symbol arrays that sparse_attn_fwd, sparse_gemm_q and sparse_gemm_o read at the following steps.

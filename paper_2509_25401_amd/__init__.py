@@ -13,6 +13,9 @@ from .binding import (  # noqa: F401
     sparse_gemm_q,
     sparse_gemm_o,
     sparse_symbols_update,
+    sparse_attn_fwd_forecast,
+    sparse_op_reuse,
+    sparse_taylor_coefficients,
     sparse_attn_profile_begin,
     sparse_attn_profile_end,
     sparse_attn_pack_mask,

@@ -57,6 +57,12 @@ def load_library():
     lib.sparse_gemm_o_stream.argtypes = [vp] * 4 + [i32, vp, vp] + [i32] * 6 + [vp]
     lib.sparse_gemm_o_stream.restype = i32
     f32 = ctypes.c_float
+    lib.sparse_attn_fwd_forecast.argtypes = [vp] * 7 + [i32, vp] + [i32] * 6 + [vp]
+    lib.sparse_attn_fwd_forecast.restype = i32
+    lib.sparse_op_reuse.argtypes = [vp, vp, i32, vp, ctypes.c_ulonglong, vp]
+    lib.sparse_op_reuse.restype = i32
+    lib.sparse_taylor_coefficients.argtypes = [i32, f32, vp]
+    lib.sparse_taylor_coefficients.restype = None
     lib.sparse_symbols_update.argtypes = [vp] * 4 + [i32] * 6 + [f32] * 3
     lib.sparse_symbols_update.restype = i32
     lib.sparse_symbols_update_stream.argtypes = [vp] * 4 + [i32] * 6 + [f32] * 3 + [vp]
@@ -169,6 +175,52 @@ def sparse_gemm_o(O, W, bias, cache_flags, select_cached, addend, Out, block_q, 
     if rc != 0:
         _raise(rc)
     return Out
+
+
+def _term_arrays(terms, coef, name):
+    if len(terms) != len(coef) or not terms:
+        raise ValueError("one coefficient per term, at least one term")
+    ptrs = (ctypes.c_void_p * len(terms))(*[_dev_ptr(t, f"{name}[{d}]").value for d, t in enumerate(terms)])
+    cf = (ctypes.c_float * len(coef))(*[float(c) for c in coef])
+    return ptrs, cf
+
+
+def sparse_attn_fwd_forecast(Q, K, V, cache_flags, kv_mask, O_terms, coef, O, block_q, block_k, stream=None):
+    """Algorithm 1 with OP_reuse = sum_d coef[d] * O_terms[d] in the cache branch (Taylor forecast of cached blocks).
+    O_terms: list of device tensors bf16 [B,H,L,D]; coef: list of floats (see sparse_taylor_coefficients)."""
+    B, H, L, D = Q.shape
+    for t in O_terms:
+        if tuple(t.shape) != (B, H, L, D):
+            raise ValueError("every term must have the shape of Q")
+    ptrs, cf = _term_arrays(O_terms, coef, "O_terms")
+    rc = load_library().sparse_attn_fwd_forecast(_dev_ptr(Q, "Q"), _dev_ptr(K, "K"), _dev_ptr(V, "V"),
+                                                 _dev_ptr(cache_flags, "cache_flags", True),
+                                                 _dev_ptr(kv_mask, "kv_mask", True), ptrs, cf, len(O_terms),
+                                                 _dev_ptr(O, "O"), int(B), int(H), int(L), int(D), int(block_q),
+                                                 int(block_k), _stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
+    return O
+
+
+def sparse_op_reuse(terms, coef, out, stream=None):
+    """out = sum_d coef[d] * terms[d], element-wise on device bf16 tensors of one shape (a term may be `out`)."""
+    n = out.numel()
+    for t in terms:
+        if t.numel() != n:
+            raise ValueError("every term must have as many elements as out")
+    ptrs, cf = _term_arrays(terms, coef, "terms")
+    rc = load_library().sparse_op_reuse(ptrs, cf, len(terms), _dev_ptr(out, "out"), int(n), _stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
+    return out
+
+
+def sparse_taylor_coefficients(order, steps):
+    """[steps^d / d! for d = 0..order] as the library computes them (float32 values)."""
+    buf = (ctypes.c_float * (int(order) + 1))()
+    load_library().sparse_taylor_coefficients(int(order), float(steps), buf)
+    return [float(x) for x in buf]
 
 
 def sparse_symbols_update(Q, K, cache_flags, kv_mask, block, text_tokens, tau_c, tau_kv, s_q=0.0, stream=None):

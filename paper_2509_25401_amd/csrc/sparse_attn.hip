@@ -54,6 +54,7 @@ constexpr int kMaxTq = 16384;
 constexpr unsigned kCopyFlag = 0x80000000u;
 constexpr int kHwRegXccId = (3 << 11) | 20;   // s_getreg operand: 4 bits at offset 0 of hardware register 20 (XCC_ID)
 constexpr int kOrderThreads = 1024;
+constexpr int kMaxTerms = 4;            // stored feature + up to three derivatives
 constexpr int kMfmaPrio = 1;            // wave priority while it feeds the matrix pipe
 constexpr float kRescaleLog2 = 8.0f;    // how far (log2) a score may exceed the exponent's reference before it moves
 
@@ -73,6 +74,11 @@ struct AttnParams {
   int nw32;
   int do_copy;             // 0: cached blocks are already in place
   float scale_log2;        // log2(e) / sqrt(D)
+  // OP_reuse as a Taylor forecast: cached block = sum_d coef[d] * term[d]; term[0] is O_cache.
+  // n_terms == 0 selects the plain bit-exact copy.
+  const char* term[kMaxTerms - 1];
+  float coef[kMaxTerms];
+  int n_terms;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -265,10 +271,30 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
 
     if (entry & kCopyFlag) {
       // cache-then-reuse: O_i <- cached O_i, bit exact
-      if (p.do_copy) {
+      constexpr int NV = BQ * ROWB / 16;
+      if (p.n_terms > 0) {
+        // forecast: fp32 sum of the scaled terms in order, rounded once to bf16
+        const bf16x8* t0 = (const bf16x8*)(p.O_cache + blk_off);
+        bf16x8* dst = (bf16x8*)(p.O + blk_off);
+        for (int t = tid; t < NV; t += NT) {
+          const bf16x8 a = t0[t];
+          float acc[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[e] = p.coef[0] * (float)a[e];
+          for (int d = 1; d < p.n_terms; ++d) {
+            const bf16x8 b = ((const bf16x8*)(p.term[d - 1] + blk_off))[t];
+            const float c = p.coef[d];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(c, (float)b[e], acc[e]);
+          }
+          bf16x8 r;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) r[e] = (__bf16)acc[e];
+          dst[t] = r;
+        }
+      } else if (p.do_copy) {
         const u32x4* src = (const u32x4*)(p.O_cache + blk_off);
         u32x4* dst = (u32x4*)(p.O + blk_off);
-        constexpr int NV = BQ * ROWB / 16;
 #pragma unroll 4
         for (int t = tid; t < NV; t += NT) dst[t] = src[t];
       }
@@ -600,9 +626,15 @@ int launch_attn(const AttnParams& p, int grid, hipStream_t stream) {
   return 0;
 }
 
+struct Forecast {
+  const void* const* terms;   // host array of n device pointers
+  const float* coef;          // host array of n weights
+  int n;
+};
+
 int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags, const uint8_t* kv_mask,
         const void* O_cache, void* O, int B, int H, int L, int D, int bq, int bk, hipStream_t stream, float* plan_ms,
-        float* attn_ms, bool timed) {
+        float* attn_ms, bool timed, const Forecast* fc = nullptr) {
   Shape s;
   if (int rc = check_shape(B, H, L, D, bq, bk, true, &s)) return rc;
   if (!Q || !K || !V || !O) return fail(SPARSE_ATTN_ERR_INVALID, "Q, K, V and O must not be NULL");
@@ -613,6 +645,18 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
     return fail(SPARSE_ATTN_ERR_INVALID, "O_cache must be O itself or must not overlap O");
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O | (uintptr_t)O_cache) & 15)
     return fail(SPARSE_ATTN_ERR_INVALID, "tensor base pointers must be 16-byte aligned");
+  if (fc) {
+    if (fc->n < 1 || fc->n > kMaxTerms)
+      return fail(SPARSE_ATTN_ERR_UNSUPPORTED, "n_terms=%d must be between 1 and %d", fc->n, kMaxTerms);
+    if (!fc->terms || !fc->coef) return fail(SPARSE_ATTN_ERR_INVALID, "O_terms and coef must not be NULL");
+    for (int d = 0; d < fc->n; ++d) {
+      if (!fc->terms[d]) return fail(SPARSE_ATTN_ERR_INVALID, "O_terms[%d] must not be NULL", d);
+      if ((uintptr_t)fc->terms[d] & 15) return fail(SPARSE_ATTN_ERR_INVALID, "O_terms[%d] must be 16-byte aligned", d);
+      if (overlaps(O, fc->terms[d], tensor_bytes)) return fail(SPARSE_ATTN_ERR_INVALID, "O_terms[%d] must not overlap O", d);
+      if (!(fc->coef[d] == fc->coef[d]) || fc->coef[d] - fc->coef[d] != 0.f)
+        return fail(SPARSE_ATTN_ERR_INVALID, "coef[%d] must be finite", d);
+    }
+  }
 
   void* ws = nullptr;
   if (int rc = sa_get_scratch(workspace_bytes(s), stream, &ws)) return rc;
@@ -668,6 +712,19 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
   p.L = L;
   p.nw32 = s.nw32;
   p.do_copy = (O_cache != nullptr && O_cache != O) ? 1 : 0;
+  for (int d = 0; d < kMaxTerms; ++d) p.coef[d] = 0.f;
+  for (int d = 0; d + 1 < kMaxTerms; ++d) p.term[d] = nullptr;
+  p.n_terms = 0;
+  if (fc) {
+    p.O_cache = (const char*)fc->terms[0];
+    if (fc->n == 1 && fc->coef[0] == 1.0f) {
+      p.do_copy = 1;                       // order 0 with weight 1 is the plain copy
+    } else {
+      p.n_terms = fc->n;
+      for (int d = 0; d < fc->n; ++d) p.coef[d] = fc->coef[d];
+      for (int d = 1; d < fc->n; ++d) p.term[d - 1] = (const char*)fc->terms[d];
+    }
+  }
   p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
   // persistent grid: two workgroups per CU (64 KiB of LDS each), fewer if there are fewer items
   const int grid = s.N < 2 * cus ? s.N : 2 * cus;
@@ -718,6 +775,14 @@ int sparse_attn_fwd_timed(const void* Q, const void* K, const void* V, const uin
                           int block_q, int block_k, void* hip_stream, float* plan_ms, float* attn_ms) {
   return run(Q, K, V, cache_flags, kv_mask, O_cache, O, B, H, L, D, block_q, block_k, (hipStream_t)hip_stream,
              plan_ms, attn_ms, true);
+}
+
+int sparse_attn_fwd_forecast(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
+                             const uint8_t* kv_mask, const void* const* O_terms, const float* coef, int n_terms, void* O,
+                             int B, int H, int L, int D, int block_q, int block_k, void* hip_stream) {
+  const Forecast fc = {O_terms, coef, n_terms};
+  return run(Q, K, V, cache_flags, kv_mask, nullptr, O, B, H, L, D, block_q, block_k, (hipStream_t)hip_stream, nullptr,
+             nullptr, false, &fc);
 }
 
 size_t sparse_attn_workspace_bytes(int B, int H, int L, int block_q, int block_k) {

@@ -22,14 +22,14 @@ def _declared_functions():
             continue
         text = open(os.path.join(inc, fn)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names += re.findall(r"\b(sparse_(?:attn|gemm|symbols)_\w+)\s*\(", text)
+        names += re.findall(r"\b(sparse_(?:attn|gemm|symbols|op|taylor)_\w+)\s*\(", text)
     return sorted(set(names))
 
 
 def test_library_exports_every_declared_symbol():
     lib = pkg.load_library()
     names = _declared_functions()
-    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and "sparse_gemm_o" in names and "sparse_symbols_update" in names and len(names) >= 14
+    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and "sparse_gemm_o" in names and "sparse_symbols_update" in names and "sparse_op_reuse" in names and "sparse_taylor_coefficients" in names and len(names) >= 17
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
     assert pkg.sparse_attn_version() >= 100
@@ -152,3 +152,55 @@ def _symbols(B=1, H=1, L=512, D=128, blk=128, text=128, tau_c=0.5, tau_kv=0.1, s
 def test_symbols_argument_validation_precedes_any_device_work(kw, code):
     assert _symbols(**kw) == code
     assert pkg.sparse_attn_last_error() != ""
+
+
+def _ptr_array(vals):
+    arr = (ctypes.c_void_p * len(vals))(*vals)
+    return arr
+
+
+def _op_reuse(n_terms=2, terms=(0x10000, 0x20000000), coef=(1.0, 0.5), out=ctypes.c_void_p(0x90000000), n=1024,
+              null_terms=False, null_coef=False):
+    t = None if null_terms else _ptr_array(list(terms))
+    c = None if null_coef else (ctypes.c_float * len(coef))(*coef)
+    return pkg.load_library().sparse_op_reuse(t, c, n_terms, out, n, None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n_terms=0), -2), (dict(n_terms=5), -2),
+    (dict(null_terms=True), -1), (dict(null_coef=True), -1), (dict(out=None), -1),
+    (dict(n=0), -1), (dict(n=1001), -1),
+    (dict(terms=(0x10000, None)), -1), (dict(terms=(0x10004, 0x20000000)), -1),
+    (dict(out=ctypes.c_void_p(0x90000008)), -1),
+    (dict(terms=(0x10000, 0x90000000 + 64)), -1),          # overlaps out without being out
+    (dict(coef=(1.0, float("inf"))), -1), (dict(coef=(float("nan"), 1.0)), -1),
+])
+def test_op_reuse_argument_validation_precedes_any_device_work(kw, code):
+    assert _op_reuse(**kw) == code
+    assert pkg.sparse_attn_last_error() != ""
+
+
+def _forecast(n_terms=2, terms=(0x30000000, 0x40000000), coef=(1.0, 2.0), O=ctypes.c_void_p(0x90000000), null_terms=False,
+              B=1, H=1, L=128, D=128, bq=128, bk=128):
+    t = None if null_terms else _ptr_array(list(terms))
+    c = (ctypes.c_float * len(coef))(*coef)
+    return pkg.load_library().sparse_attn_fwd_forecast(FAKE, ctypes.c_void_p(0x20000000), ctypes.c_void_p(0x28000000), None, None,
+                                                       t, c, n_terms, O, B, H, L, D, bq, bk, None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n_terms=0), -2), (dict(n_terms=5), -2), (dict(null_terms=True), -1),
+    (dict(terms=(0x30000000, None)), -1), (dict(terms=(0x30000004, 0x40000000)), -1),
+    (dict(terms=(0x30000000, 0x90000000)), -1),            # a term overlaps O
+    (dict(coef=(1.0, float("nan"))), -1),
+    (dict(L=100), -1), (dict(D=96), -2),
+])
+def test_forecast_argument_validation_precedes_any_device_work(kw, code):
+    assert _forecast(**kw) == code
+    assert pkg.sparse_attn_last_error() != ""
+
+
+def test_taylor_coefficients_match_the_oracle():
+    import oracle
+    for order, k in ((0, 3.0), (1, 2.0), (2, 2.5), (3, 4.0)):
+        assert pkg.sparse_taylor_coefficients(order, k) == [float(np.float32(c)) for c in oracle.taylor_coefficients(order, k)]

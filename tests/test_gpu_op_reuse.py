@@ -1,0 +1,105 @@
+"""GPU parity of OP_reuse (Taylor forecast): the element-wise kernel and the fused cache branch of the attention
+kernel, against the fp64 oracle.  The kernels sum in fp32 and round once; a result may differ from the fp64 one by
+one bf16 step only where the fp64 value lies within fp32 rounding of a bf16 rounding boundary."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_25401_amd as pkg
+from paper_2509_25401_amd import synth
+from gpu_utils import dev, up_bf16, up_u8, down_bits, check_against_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def check_forecast(got_bits, ref_f64, terms, coef, label):
+    got = synth.bf16_bits_to_f32(got_bits).astype(np.float64)
+    scale = sum(abs(c) * np.abs(synth.bf16_bits_to_f32(t).astype(np.float64)) for c, t in zip(coef, terms))
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref_f64), 1e-38))) - 7)
+    tol = 0.5 * ulp + 8 * 2.0 ** -24 * scale + 1e-38
+    err = np.abs(got - ref_f64)
+    same = (got_bits == oracle.op_reuse(terms, coef)[1]).mean()
+    print(f"[op_reuse] {label}: bit-identical to the rounded oracle {same * 100:.4f} %, max err/tol {(err / tol).max():.3f}", flush=True)
+    assert (err <= tol).all(), f"{label}: forecast differs from the oracle by more than one rounding"
+    assert same > 0.999
+
+
+@pytest.mark.parametrize("n_terms,k", [(1, 0.0), (2, 1.0), (3, 2.0), (4, 3.0)])
+def test_elementwise_matches_oracle(n_terms, k):
+    rng = np.random.default_rng(synth.BASE_SEED + 40 + n_terms)
+    shape = (3, 1000, 24)                                      # 72000 elements: ragged against the 256-thread grid
+    terms = [synth.normal_bf16(rng, shape) for _ in range(n_terms)]
+    coef = pkg.sparse_taylor_coefficients(n_terms - 1, k) if n_terms > 1 else [0.75]
+    d_terms = [up_bf16(t) for t in terms]
+    out = torch.zeros(shape, dtype=torch.bfloat16, device=dev())
+    pkg.sparse_op_reuse(d_terms, coef, out)
+    torch.cuda.synchronize()
+    ref, _ = oracle.op_reuse(terms, coef)
+    check_forecast(down_bits(out), ref, terms, coef, f"elementwise n_terms={n_terms}")
+    # in place on the first term
+    pkg.sparse_op_reuse(d_terms, coef, d_terms[0])
+    torch.cuda.synchronize()
+    assert (down_bits(d_terms[0]) == down_bits(out)).all()
+
+
+def test_identity_is_bit_exact_and_large_sizes_are_covered():
+    rng = np.random.default_rng(synth.BASE_SEED + 50)
+    n = 8192 * 256 * 8 * 2 + 8 * 13                            # more vectors than one grid pass, plus a ragged tail
+    x = synth.normal_bf16(rng, (n,))
+    y = synth.normal_bf16(rng, (n,))
+    dx, dy = up_bf16(x), up_bf16(y)
+    out = torch.zeros(n, dtype=torch.bfloat16, device=dev())
+    pkg.sparse_op_reuse([dx], [1.0], out)
+    torch.cuda.synchronize()
+    assert (down_bits(out) == x).all()
+    pkg.sparse_op_reuse([dx, dy], [1.0, -0.5], out)
+    torch.cuda.synchronize()
+    ref, _ = oracle.op_reuse([x, y], [1.0, -0.5])
+    check_forecast(down_bits(out), ref, [x, y], [1.0, -0.5], "elementwise 33M elements")
+
+
+@pytest.mark.parametrize("D,bq,bk,n_terms", [(128, 128, 128, 2), (64, 64, 128, 3), (128, 64, 64, 4), (128, 128, 64, 1)])
+def test_attention_cache_branch_forecasts(D, bq, bk, n_terms):
+    w = synth.random_case(synth.BASE_SEED + 60 + n_terms, 2, 3, 1024, D, bq, bk, keep=0.5, cached_frac=0.4)
+    rng = np.random.default_rng(synth.BASE_SEED + 70 + n_terms)
+    terms = [w.O_cache] + [synth.normal_bf16(rng, w.Q.shape) for _ in range(n_terms - 1)]
+    coef = pkg.sparse_taylor_coefficients(n_terms - 1, 2.0)
+    if n_terms == 1:
+        coef = [1.0]
+    mask_host = pkg.sparse_attn_pack_mask(w.M_s)
+    O = torch.from_numpy(np.full(w.Q.shape, 0x4242, dtype=np.uint16).view(np.int16)).view(torch.bfloat16).to(dev())
+    pkg.sparse_attn_fwd_forecast(up_bf16(w.Q), up_bf16(w.K), up_bf16(w.V), up_u8(w.cache_flags), up_u8(mask_host),
+                                 [up_bf16(t) for t in terms], coef, O, bq, bk)
+    torch.cuda.synchronize()
+    got = down_bits(O)
+    ref, ref_bits = oracle.attention_with_forecast(w.Q, w.K, w.V, w.cache_flags, oracle.pack_symbols(w.M_s), terms, coef, bq, bk)
+    rows = np.repeat(w.cache_flags != 0, bq, axis=2)
+    assert rows.any() and (~rows).any()
+    if n_terms == 1:
+        assert (got[rows] == w.O_cache[rows]).all()            # order 0 with weight 1: the bit-exact copy
+    else:
+        check_forecast(got[rows], ref[rows], [t[rows] for t in terms], coef, f"fused D{D} {bq}x{bk} n_terms={n_terms}")
+    # computed blocks: the usual bar
+    err = np.abs(synth.bf16_bits_to_f32(got[~rows]).astype(np.float64) - ref[~rows])
+    assert err.max() <= 1e-2 and err.mean() <= 1e-3
+
+
+def test_forecast_feeds_the_output_projection():
+    """Dispatch step of Section 3.5: Out is initialised with OP_reuse(B_c terms), GEMM-O adds the computed heads."""
+    rng = np.random.default_rng(synth.BASE_SEED + 80)
+    B, H, L, D, C, bq = 1, 4, 512, 128, 256, 128
+    O = synth.normal_bf16(rng, (B, H, L, D))
+    W = synth.f32_to_bf16_bits((rng.standard_normal((C, H * D)) / np.sqrt(H * D)).astype(np.float32))
+    flags = (rng.random((B, H, L // bq)) < 0.5).astype(np.uint8)
+    bc = [synth.normal_bf16(rng, (B, L, C)) for _ in range(2)]
+    coef = pkg.sparse_taylor_coefficients(1, 3.0)
+    Out = torch.zeros((B, L, C), dtype=torch.bfloat16, device=dev())
+    pkg.sparse_op_reuse([up_bf16(t) for t in bc], coef, Out)
+    pkg.sparse_gemm_o(up_bf16(O), up_bf16(W), None, up_u8(flags), 0, Out, Out, bq)
+    torch.cuda.synchronize()
+    _, addend_bits = oracle.op_reuse(bc, coef)
+    ref, _ = oracle.gemm_o(O, W, None, flags, 0, addend_bits, bq)
+    err = np.abs(synth.bf16_bits_to_f32(down_bits(Out)).astype(np.float64) - ref)
+    print(f"[op_reuse] forecast bias + GEMM-O: max-abs {err.max():.3e}", flush=True)
+    assert err.max() <= 6e-2 and err.mean() <= 1e-2             # bf16 rounding of values of size ~4
