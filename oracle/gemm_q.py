@@ -23,9 +23,32 @@ def _narrow(x):
     return ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)).astype(np.uint16)
 
 
-def gemm_q(X, W, bias, cache_flags, block_q, H, D, Q_init_bits=None):
+def rms_norm(y, weight, eps):
+    """Token-wise RMS normalisation over the last axis: y / sqrt(mean(y^2) + eps) * weight."""
+    ms = (y * y).mean(axis=-1, keepdims=True)
+    out = y / np.sqrt(ms + eps)
+    return out if weight is None else out * weight
+
+
+def rope(y, cos, sin):
+    """Rotary position encoding on adjacent channel pairs: (y[2m], y[2m+1]) of token l is rotated by the
+    angle whose cosine and sine are cos[l, m], sin[l, m].  y: [L, D]; cos, sin: [L, D/2]."""
+    even, odd = y[..., 0::2], y[..., 1::2]
+    out = np.empty_like(y)
+    out[..., 0::2] = even * cos - odd * sin
+    out[..., 1::2] = even * sin + odd * cos
+    return out
+
+
+def gemm_q(X, W, bias, cache_flags, block_q, H, D, Q_init_bits=None, norm_weight=None, eps=None, rope_cos=None,
+           rope_sin=None):
     """X: uint16 bf16 bits [B, L, C]; W: [H*D, C] (one row per output feature, as a Linear layer
     stores it); bias: [H*D] or None; cache_flags: uint8 [B, H, L/block_q] or None.
+
+    With eps given, the projection of every (token, head) is RMS-normalised over its D channels
+    (norm_weight: uint16 bf16 bits [D] or None for ones) and, with rope_cos / rope_sin (float [L, D/2])
+    given, rotated -- Equation 2's OP_RoPE(OP_RMSNorm(X W)), both token-wise -- before the one
+    rounding to bf16.
 
     Returns (Q_f64, Q_bits) of shape [B, H, L, D].  Skipped blocks keep Q_init_bits (zeros if
     not given) in Q_bits and its widened value in Q_f64.
@@ -49,6 +72,10 @@ def gemm_q(X, W, bias, cache_flags, block_q, H, D, Q_init_bits=None):
             full = Xf[b] @ Wf[h * D:(h + 1) * D].T          # [L, D]
             if bf is not None:
                 full = full + bf[h * D:(h + 1) * D][None, :]
+            if eps is not None:
+                full = rms_norm(full, None if norm_weight is None else _widen(norm_weight), float(eps))
+            if rope_cos is not None:
+                full = rope(full, np.asarray(rope_cos, dtype=np.float64), np.asarray(rope_sin, dtype=np.float64))
             for i in range(Tq):
                 if cache_flags is not None and cache_flags[b, h, i]:
                     continue

@@ -81,3 +81,63 @@ def test_linearity_and_bias():
     X2 = synth.f32_to_bf16_bits(2.0 * synth.bf16_bits_to_f32(X))      # exact in bf16
     Q3, _ = oracle.gemm_q(X2, W, None, None, bq, H, D)
     assert np.abs(Q3 - 2.0 * Q1).max() < 1e-12
+
+
+# ---- fused token-wise RMSNorm + RoPE (Equation 2) ----
+
+def _angles(L, D, base=10000.0):
+    pos = np.arange(L, dtype=np.float64)[:, None]
+    freq = base ** (-np.arange(D // 2, dtype=np.float64) / (D // 2))[None, :]
+    return pos * freq
+
+
+def test_rms_norm_invariants():
+    r = np.random.default_rng(21)
+    y = r.standard_normal((5, 7, 16)) * 3.0
+    out = oracle.rms_norm(y, None, 0.0)
+    assert np.allclose((out * out).mean(axis=-1), 1.0, atol=1e-12)            # unit mean square
+    assert np.allclose(oracle.rms_norm(4.0 * y, None, 0.0), out, atol=1e-12)  # scale invariant without eps
+    g = r.standard_normal(16)
+    assert np.allclose(oracle.rms_norm(y, g, 0.0), out * g, atol=1e-12)
+    # with eps: explicit loop on one token
+    v = y[1, 2]
+    ms = sum(x * x for x in v) / 16
+    assert np.allclose(oracle.rms_norm(y, g, 1e-3)[1, 2], [x / np.sqrt(ms + 1e-3) * gg for x, gg in zip(v, g)], atol=1e-12)
+
+
+def test_rope_is_a_rotation_with_the_relative_position_property():
+    r = np.random.default_rng(22)
+    L, D = 12, 8
+    ang = _angles(L, D)
+    q, k = r.standard_normal((L, D)), r.standard_normal((L, D))
+    rq, rk = oracle.rope(q, np.cos(ang), np.sin(ang)), oracle.rope(k, np.cos(ang), np.sin(ang))
+    assert np.allclose(rq[0], q[0]) and np.allclose(rk[0], k[0])              # position 0: zero angle, identity
+    pair_norm = lambda x: x[:, 0::2] ** 2 + x[:, 1::2] ** 2
+    assert np.allclose(pair_norm(rq), pair_norm(q), atol=1e-12)               # every pair is rotated, not scaled
+    # scores depend on the position difference only: the same vectors placed 3 positions later give the same product
+    a, b = q[4], k[7]
+    def at(v, pos):
+        return oracle.rope(v[None, :], np.cos(ang[pos:pos + 1]), np.sin(ang[pos:pos + 1]))[0]
+    assert abs(at(a, 1) @ at(b, 4) - at(a, 6) @ at(b, 9)) < 1e-12
+    assert abs(at(a, 1) @ at(b, 4) - at(a, 1) @ at(b, 5)) > 1e-6
+    # complex-number form of the same rotation
+    z = (q[:, 0::2] + 1j * q[:, 1::2]) * np.exp(1j * ang)
+    assert np.allclose(rq[:, 0::2], z.real) and np.allclose(rq[:, 1::2], z.imag)
+
+
+def test_fused_projection_reduces_to_its_parts():
+    B, L, C, H, D, bq = 1, 32, 24, 2, 8, 16
+    X, W, b, flags = _case(23, B, L, C, H, D, bq, cached=0.3)
+    r = np.random.default_rng(24)
+    g = synth.normal_bf16(r, (D,))
+    ang = _angles(L, D)
+    plain, _ = oracle.gemm_q(X, W, b, None, bq, H, D)
+    fused, bits = oracle.gemm_q(X, W, b, flags, bq, H, D, norm_weight=g, eps=1e-6, rope_cos=np.cos(ang), rope_sin=np.sin(ang))
+    want = np.stack([oracle.rope(oracle.rms_norm(plain[0, h], bits_to_f64(g), 1e-6), np.cos(ang), np.sin(ang)) for h in range(H)])[None]
+    live = np.repeat(flags == 0, bq, axis=2)
+    assert np.abs(fused[live] - want[live]).max() < 1e-12
+    assert (fused[~live] == 0).all() and (bits[~live] == 0).all()             # skipped tiles untouched
+    # zero angles and unit gain: only the normalisation is left
+    zero = np.zeros_like(ang)
+    n_only, _ = oracle.gemm_q(X, W, b, None, bq, H, D, eps=0.0, rope_cos=np.cos(zero), rope_sin=np.sin(zero))
+    assert np.allclose((n_only ** 2).mean(axis=-1), 1.0, atol=1e-12)
