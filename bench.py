@@ -185,7 +185,22 @@ def main():
             log(f"gemm_q cached {gq[-1]['cached_frac']:.2f}: {ms:.3f} ms, {gq[-1]['tflops_on_computed_tiles']:.0f} TFLOP/s, "
                 f"{gq[-1]['speedup_vs_dense']:.2f}x (ideal {gq[-1]['ideal_speedup']:.2f}x)")
         extra["gemm_q"] = gq
-        del Xp
+        # the same projection with the token-wise RMSNorm + RoPE of Equation 2 fused into its epilogue
+        gain = torch.ones(w.D, device=dev, dtype=torch.bfloat16)
+        ang = torch.arange(w.L, device=dev, dtype=torch.float32)[:, None] * (10000.0 ** (-torch.arange(w.D // 2, device=dev, dtype=torch.float32) / (w.D // 2)))[None, :]
+        rc, rs = torch.cos(ang).contiguous(), torch.sin(ang).contiguous()
+        for _ in range(2):
+            pkg.sparse_gemm_q_norm_rope(Xp, Wp, None, gain, 1e-6, rc, rs, None, O, w.block_q)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            pkg.sparse_gemm_q_norm_rope(Xp, Wp, None, gain, 1e-6, rc, rs, None, O, w.block_q)
+        e1.record()
+        torch.cuda.synchronize()
+        extra["gemm_q_norm_rope_dense_ms"] = e0.elapsed_time(e1) / 10
+        log(f"gemm_q + RMSNorm + RoPE fused, no tile cached: {extra['gemm_q_norm_rope_dense_ms']:.3f} ms (plain {gq[0]['ms']:.3f} ms)")
+        del Xp, gain, ang, rc, rs
         # the step after attention (GEMM-O stage 2, Section 3.5): heads whose flag is set are skipped along the
         # reduction axis and their contribution comes from the cached bias B_c (the addend)
         Wo = (torch.randn((C, w.H * w.D), device=dev, generator=g) / (w.H * w.D) ** 0.5).to(torch.bfloat16)

@@ -111,6 +111,24 @@ int sparse_gemm_q_stream(const void* X, const void* W, const void* bias, const u
                          int B, int L, int C, int H, int D, int block_q, void* hip_stream);
 
 /*
+ * GEMM-Q with the two token-wise operations of Equation 2 fused into its epilogue:
+ *     Q[b,h,token,:] = OP_RoPE(OP_RMSNorm(X[b,token,:] . W_h^T + bias_h))
+ * for every (b,h,i) whose flag is clear (flagged tiles return at once, as in sparse_gemm_q).
+ *   OP_RMSNorm  y / sqrt(mean over the head's D channels of y^2 + eps) * norm_weight
+ *   OP_RoPE     adjacent channel pairs (2m, 2m+1) of token l are rotated by the angle whose cosine and sine are
+ *               rope_cos[l, m] and rope_sin[l, m]:  (y0, y1) -> (y0 cos - y1 sin, y0 sin + y1 cos)
+ * fp32 throughout after the bf16 MFMA products, one rounding to bf16 at the end.
+ *   norm_weight  device, bf16 [D] (shared by all heads), or NULL for ones
+ *   eps          finite, >= 0
+ *   rope_cos, rope_sin  device, fp32 [L, D/2], 8-byte aligned (shared by batches and heads), or both NULL
+ *                for no rotation
+ * Everything else as for sparse_gemm_q_stream.  Allocates nothing.
+ */
+int sparse_gemm_q_norm_rope(const void* X, const void* W, const void* bias, const void* norm_weight, float eps,
+                            const float* rope_cos, const float* rope_sin, const uint8_t* cache_flags, void* Q,
+                            int B, int L, int C, int H, int D, int block_q, void* hip_stream);
+
+/*
  * Sparse output projection (GEMM-O, Section 3.5, Observation 3 / Equations 3-4): the step right after
  * the attention call.  For every token block i and every output channel n
  *     Out[b, token, n] = addend[b, token, n] + bias[n]

@@ -52,6 +52,8 @@ def load_library():
     lib.sparse_gemm_q.restype = i32
     lib.sparse_gemm_q_stream.argtypes = [vp] * 5 + [i32] * 6 + [vp]
     lib.sparse_gemm_q_stream.restype = i32
+    lib.sparse_gemm_q_norm_rope.argtypes = [vp] * 4 + [ctypes.c_float] + [vp] * 4 + [i32] * 6 + [vp]
+    lib.sparse_gemm_q_norm_rope.restype = i32
     lib.sparse_gemm_o.argtypes = [vp] * 4 + [i32, vp, vp] + [i32] * 6
     lib.sparse_gemm_o.restype = i32
     lib.sparse_gemm_o_stream.argtypes = [vp] * 4 + [i32, vp, vp] + [i32] * 6 + [vp]
@@ -153,6 +155,29 @@ def sparse_gemm_q(X, W, bias, cache_flags, Q, block_q, stream=None):
     rc = load_library().sparse_gemm_q_stream(_dev_ptr(X, "X"), _dev_ptr(W, "W"), _dev_ptr(bias, "bias", True),
                                              _dev_ptr(cache_flags, "cache_flags", True), _dev_ptr(Q, "Q"),
                                              int(B), int(L), int(C), int(H), int(D), int(block_q), _stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
+    return Q
+
+
+def sparse_gemm_q_norm_rope(X, W, bias, norm_weight, eps, rope_cos, rope_sin, cache_flags, Q, block_q, stream=None):
+    """sparse_gemm_q with token-wise RMSNorm (norm_weight bf16 [D] or None, eps) and RoPE on adjacent channel pairs
+    (rope_cos, rope_sin fp32 [L, D/2], or both None) fused into the epilogue (Equation 2)."""
+    B, L, C = X.shape
+    _, H, _, D = Q.shape
+    if tuple(W.shape) != (H * D, C) or tuple(Q.shape) != (B, H, L, D):
+        raise ValueError("shapes of X [B,L,C], W [H*D,C] and Q [B,H,L,D] do not fit together")
+    import torch
+    for t, name in ((rope_cos, "rope_cos"), (rope_sin, "rope_sin")):
+        if t is not None and (t.dtype != torch.float32 or tuple(t.shape) != (L, D // 2)):
+            raise ValueError(f"{name} must be float32 [L, D/2]")
+    if norm_weight is not None and (norm_weight.dtype != torch.bfloat16 or norm_weight.numel() != D):
+        raise ValueError("norm_weight must be bfloat16 [D]")
+    rc = load_library().sparse_gemm_q_norm_rope(_dev_ptr(X, "X"), _dev_ptr(W, "W"), _dev_ptr(bias, "bias", True),
+                                                _dev_ptr(norm_weight, "norm_weight", True), float(eps),
+                                                _dev_ptr(rope_cos, "rope_cos", True), _dev_ptr(rope_sin, "rope_sin", True),
+                                                _dev_ptr(cache_flags, "cache_flags", True), _dev_ptr(Q, "Q"),
+                                                int(B), int(L), int(C), int(H), int(D), int(block_q), _stream_ptr(stream))
     if rc != 0:
         _raise(rc)
     return Q

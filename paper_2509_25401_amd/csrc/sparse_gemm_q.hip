@@ -36,12 +36,17 @@ struct GemmQParams {
   const uint8_t* flags;  // [B, H, Tq] or nullptr
   char* Q;             // bf16 [B, H, L, D]
   int H, L, C, Tq;
+  // fused epilogue (NORM_ROPE instantiations only)
+  const uint16_t* norm_w;   // bf16 [D] or nullptr (= ones)
+  const float* rope_cos;    // fp32 [L, D/2] or nullptr (= no rotation)
+  const float* rope_sin;
+  float eps;
 };
 
 // 16-byte chunk permutation of a 128-byte tile row (two rows share a 256-byte bank line)
 __device__ __forceinline__ int row_swizzle(int row) { return (row >> 1) & 7; }
 
-template <int BQ, int D>
+template <int BQ, int D, bool NORM_ROPE>
 __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(const GemmQParams p) {
   constexpr int WM = BQ / 64;              // waves along tokens
   constexpr int WN = D / 64;               // waves along head channels
@@ -165,24 +170,87 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
   // epilogue: lane holds token l32 (+32*c) and, per accumulator quad q4, head channels
   // 32*a + 8*q4 + 4*half + 0..3 of this wave's corner
   char* qrow0 = p.Q + (((size_t)b * p.H + h) * p.L + (size_t)i * BQ + wm * 64 + l32) * (size_t)(D * 2);
+  float inv_rms[2] = {1.f, 1.f};
+  if constexpr (NORM_ROPE) {
+    // Equation 2: token-wise RMS normalisation over the head's D channels, then the rotation.  The bias
+    // goes into the accumulators first; a token's sum of squares is spread over this lane's 32 values,
+    // the lane 32 further on, and (D = 128) the wave that holds the other 64 channels.
+    if (p.bias) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float bv = __builtin_bit_cast(float, (unsigned)p.bias[h * D + wn * 64 + 32 * a + 8 * q4 + 4 * half + e] << 16);
+            acc[a][0][4 * q4 + e] += bv;
+            acc[a][1][4 * q4 + e] += bv;
+          }
+    }
+    float ss[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      float v = 0.f;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v = fmaf(acc[a][c][e], acc[a][c][e], v);
+      ss[c] = v + __shfl_xor(v, 32);
+    }
+    if constexpr (WN == 2) {
+      __syncthreads();                         // every wave is done reading the operand stages
+      float* part = (float*)smem;              // [wn][BQ]
+      if (half == 0) {
+        part[wn * BQ + wm * 64 + l32] = ss[0];
+        part[wn * BQ + wm * 64 + 32 + l32] = ss[1];
+      }
+      __syncthreads();
+      ss[0] = part[wm * 64 + l32] + part[BQ + wm * 64 + l32];
+      ss[1] = part[wm * 64 + 32 + l32] + part[BQ + wm * 64 + 32 + l32];
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c) inv_rms[c] = 1.0f / sqrtf(ss[c] * (1.0f / D) + p.eps);
+  }
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
       const int d0 = wn * 64 + 32 * a + 8 * q4 + 4 * half;
       float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (p.bias) {
+      float gain[4] = {1.f, 1.f, 1.f, 1.f};
+      if constexpr (NORM_ROPE) {
+        if (p.norm_w) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) gain[e] = __builtin_bit_cast(float, (unsigned)p.norm_w[d0 + e] << 16);
+        }
+      } else if (p.bias) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           bv[e] = __builtin_bit_cast(float, (unsigned)p.bias[h * D + d0 + e] << 16);
       }
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = acc[a][c][4 * q4 + e] + bv[e];
+        if constexpr (NORM_ROPE) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) y[e] = y[e] * inv_rms[c] * gain[e];
+          if (p.rope_cos) {
+            // channels d0..d0+3 are the pairs d0/2 and d0/2 + 1 of this token
+            const size_t at = ((size_t)i * BQ + wm * 64 + 32 * c + l32) * (D / 2) + d0 / 2;
+            const float2 cs = *(const float2*)(p.rope_cos + at);
+            const float2 sn = *(const float2*)(p.rope_sin + at);
+            const float y0 = y[0] * cs.x - y[1] * sn.x, y1 = y[0] * sn.x + y[1] * cs.x;
+            const float y2 = y[2] * cs.y - y[3] * sn.y, y3 = y[2] * sn.y + y[3] * cs.y;
+            y[0] = y0; y[1] = y1; y[2] = y2; y[3] = y3;
+          }
+        }
         bf16x2 lo, hi;
-        lo[0] = (__bf16)(acc[a][c][4 * q4 + 0] + bv[0]);
-        lo[1] = (__bf16)(acc[a][c][4 * q4 + 1] + bv[1]);
-        hi[0] = (__bf16)(acc[a][c][4 * q4 + 2] + bv[2]);
-        hi[1] = (__bf16)(acc[a][c][4 * q4 + 3] + bv[3]);
+        lo[0] = (__bf16)y[0];
+        lo[1] = (__bf16)y[1];
+        hi[0] = (__bf16)y[2];
+        hi[1] = (__bf16)y[3];
         u32x2 pk;
         pk[0] = __builtin_bit_cast(unsigned, lo);
         pk[1] = __builtin_bit_cast(unsigned, hi);
@@ -191,18 +259,18 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
     }
 }
 
-template <int BQ, int D>
+template <int BQ, int D, bool NORM_ROPE>
 int launch(const GemmQParams& p, int tiles, hipStream_t stream) {
   constexpr size_t lds = 2 * (size_t)(D + BQ) * kRowB;
   constexpr int threads = (BQ / 64) * (D / 64) * 64;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_q_kernel<BQ, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_q_kernel<BQ, D, NORM_ROPE>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)lds);
     if (e != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_q_kernel<BQ, D>), dim3(tiles), dim3(threads), lds, stream, p);
+  hipLaunchKernelGGL((gemm_q_kernel<BQ, D, NORM_ROPE>), dim3(tiles), dim3(threads), lds, stream, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "gemm_q launch failed: %s", hipGetErrorString(e));
   return 0;
@@ -213,12 +281,9 @@ bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
   return x < y + nb && y < x + na;
 }
 
-}  // namespace
-
-extern "C" {
-
-int sparse_gemm_q_stream(const void* X, const void* W, const void* bias, const uint8_t* cache_flags, void* Q, int B,
-                         int L, int C, int H, int D, int block_q, void* hip_stream) {
+int gemm_q_run(const void* X, const void* W, const void* bias, const uint8_t* cache_flags, void* Q, int B, int L, int C,
+               int H, int D, int block_q, hipStream_t stream, bool norm_rope, const void* norm_weight, float eps,
+               const float* rope_cos, const float* rope_sin) {
   if (B <= 0 || L <= 0 || C <= 0 || H <= 0 || D <= 0 || block_q <= 0)
     return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: sizes must be positive (B=%d L=%d C=%d H=%d D=%d block_q=%d)", B,
                    L, C, H, D, block_q);
@@ -235,6 +300,14 @@ int sparse_gemm_q_stream(const void* X, const void* W, const void* bias, const u
   const size_t xb = (size_t)B * L * C * 2, wb = (size_t)H * D * C * 2, qb = (size_t)B * H * L * D * 2;
   if (ranges_overlap(Q, qb, X, xb) || ranges_overlap(Q, qb, W, wb))
     return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: Q must not overlap X or W");
+  if (norm_rope) {
+    if (!(eps >= 0.f) || eps - eps != 0.f) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: eps must be finite and >= 0");
+    if ((rope_cos == nullptr) != (rope_sin == nullptr))
+      return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: rope_cos and rope_sin must be given together");
+    if (((uintptr_t)rope_cos | (uintptr_t)rope_sin) & 7)
+      return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: rope_cos and rope_sin must be 8-byte aligned");
+    if ((uintptr_t)norm_weight & 1) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: norm_weight must be 2-byte aligned");
+  }
 
   GemmQParams p;
   p.X = (const char*)X;
@@ -246,16 +319,42 @@ int sparse_gemm_q_stream(const void* X, const void* W, const void* bias, const u
   p.L = L;
   p.C = C;
   p.Tq = L / block_q;
-  hipStream_t stream = (hipStream_t)hip_stream;
-  if (block_q == 128 && D == 128) return launch<128, 128>(p, (int)tiles, stream);
-  if (block_q == 128 && D == 64) return launch<128, 64>(p, (int)tiles, stream);
-  if (block_q == 64 && D == 128) return launch<64, 128>(p, (int)tiles, stream);
-  return launch<64, 64>(p, (int)tiles, stream);
+  p.norm_w = (const uint16_t*)norm_weight;
+  p.rope_cos = rope_cos;
+  p.rope_sin = rope_sin;
+  p.eps = eps;
+  if (norm_rope) {
+    if (block_q == 128 && D == 128) return launch<128, 128, true>(p, (int)tiles, stream);
+    if (block_q == 128 && D == 64) return launch<128, 64, true>(p, (int)tiles, stream);
+    if (block_q == 64 && D == 128) return launch<64, 128, true>(p, (int)tiles, stream);
+    return launch<64, 64, true>(p, (int)tiles, stream);
+  }
+  if (block_q == 128 && D == 128) return launch<128, 128, false>(p, (int)tiles, stream);
+  if (block_q == 128 && D == 64) return launch<128, 64, false>(p, (int)tiles, stream);
+  if (block_q == 64 && D == 128) return launch<64, 128, false>(p, (int)tiles, stream);
+  return launch<64, 64, false>(p, (int)tiles, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+int sparse_gemm_q_stream(const void* X, const void* W, const void* bias, const uint8_t* cache_flags, void* Q, int B,
+                         int L, int C, int H, int D, int block_q, void* hip_stream) {
+  return gemm_q_run(X, W, bias, cache_flags, Q, B, L, C, H, D, block_q, (hipStream_t)hip_stream, false, nullptr, 0.f,
+                    nullptr, nullptr);
 }
 
 int sparse_gemm_q(const void* X, const void* W, const void* bias, const uint8_t* cache_flags, void* Q, int B, int L,
                   int C, int H, int D, int block_q) {
   return sparse_gemm_q_stream(X, W, bias, cache_flags, Q, B, L, C, H, D, block_q, nullptr);
+}
+
+int sparse_gemm_q_norm_rope(const void* X, const void* W, const void* bias, const void* norm_weight, float eps,
+                            const float* rope_cos, const float* rope_sin, const uint8_t* cache_flags, void* Q, int B,
+                            int L, int C, int H, int D, int block_q, void* hip_stream) {
+  return gemm_q_run(X, W, bias, cache_flags, Q, B, L, C, H, D, block_q, (hipStream_t)hip_stream, true, norm_weight, eps,
+                    rope_cos, rope_sin);
 }
 
 }  // extern "C"

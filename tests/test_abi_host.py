@@ -204,3 +204,21 @@ def test_taylor_coefficients_match_the_oracle():
     import oracle
     for order, k in ((0, 3.0), (1, 2.0), (2, 2.5), (3, 4.0)):
         assert pkg.sparse_taylor_coefficients(order, k) == [float(np.float32(c)) for c in oracle.taylor_coefficients(order, k)]
+
+
+def _gemm_q_nr(eps=1e-6, cos=ctypes.c_void_p(0x50000000), sin=ctypes.c_void_p(0x58000000), norm=ctypes.c_void_p(0x60000000),
+               B=1, L=128, C=64, H=1, D=128, bq=128):
+    return pkg.load_library().sparse_gemm_q_norm_rope(FAKE, ctypes.c_void_p(0x20000000), None, norm, eps, cos, sin, None,
+                                                      ctypes.c_void_p(0x90000000), B, L, C, H, D, bq, None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(eps=-1.0), -1), (dict(eps=float("nan")), -1), (dict(eps=float("inf")), -1),
+    (dict(sin=None), -1), (dict(cos=None), -1),                 # only one of the two tables
+    (dict(cos=ctypes.c_void_p(0x50000004)), -1),
+    (dict(norm=ctypes.c_void_p(0x60000001)), -1),
+    (dict(L=192), -1), (dict(C=96), -2), (dict(D=96), -2),
+])
+def test_gemm_q_norm_rope_argument_validation_precedes_any_device_work(kw, code):
+    assert _gemm_q_nr(**kw) == code
+    assert pkg.sparse_attn_last_error() != ""

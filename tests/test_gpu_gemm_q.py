@@ -94,3 +94,62 @@ def test_image_dit_shape_with_flags_feeds_attention():
     got = _run(X, W, b, w.cache_flags, B, L, C, H, D, bq)
     ref, ref_bits = oracle.gemm_q(X, W, b, w.cache_flags, bq, H, D)
     _check(got, ref, ref_bits, w.cache_flags, bq, "gemm_q image-DiT")
+
+
+# ---- fused token-wise RMSNorm + RoPE epilogue (Equation 2) ----
+
+def _rope_tables(L, D, base=10000.0):
+    pos = np.arange(L, dtype=np.float64)[:, None]
+    freq = base ** (-np.arange(D // 2, dtype=np.float64) / (D // 2))[None, :]
+    ang = pos * freq
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def _run_fused(X, W, b, g, eps, cos, sin, flags, B, L, C, H, D, bq, fill=0x4242):
+    Q = torch.from_numpy(np.full((B, H, L, D), fill, dtype=np.uint16).view(np.int16)).view(torch.bfloat16).to("cuda:0")
+    dcos = None if cos is None else torch.from_numpy(cos).to("cuda:0")
+    dsin = None if sin is None else torch.from_numpy(sin).to("cuda:0")
+    pkg.sparse_gemm_q_norm_rope(up_bf16(X), up_bf16(W), None if b is None else up_bf16(b), None if g is None else up_bf16(g),
+                                eps, dcos, dsin, up_u8(flags), Q, bq)
+    torch.cuda.synchronize()
+    return down_bits(Q)
+
+
+@pytest.mark.parametrize("D,bq", [(128, 128), (64, 128), (128, 64), (64, 64)])
+def test_fused_norm_rope_small_cases(D, bq):
+    print(f"[case] gemm_q norm+rope D={D} bq={bq}", flush=True)
+    B, L, C, H = 2, 384, 320, 3
+    X, W, b, flags = _case(40 + D + bq, B, L, C, H, D, bq, cached=0.3)
+    g = synth.f32_to_bf16_bits((1.0 + 0.2 * np.random.default_rng(41).standard_normal(D)).astype(np.float32))
+    cos, sin = _rope_tables(L, D)
+    got = _run_fused(X, W, b, g, 1e-6, cos, sin, flags, B, L, C, H, D, bq)
+    ref, ref_bits = oracle.gemm_q(X, W, b, flags, bq, H, D, norm_weight=g, eps=float(np.float32(1e-6)), rope_cos=cos, rope_sin=sin)
+    _check(got, ref, ref_bits, flags, bq, f"gemm_q norm+rope D={D} bq={bq}")
+
+
+def test_fused_variants_without_gain_or_rotation():
+    B, L, C, H, D, bq = 1, 256, 128, 2, 128, 128
+    X, W, b, flags = _case(50, B, L, C, H, D, bq, cached=0.0, bias=False)
+    cos, sin = _rope_tables(L, D)
+    # normalisation only
+    got = _run_fused(X, W, None, None, 0.0, None, None, None, B, L, C, H, D, bq)
+    ref, ref_bits = oracle.gemm_q(X, W, None, None, bq, H, D, eps=0.0)
+    _check(got, ref, ref_bits, None, bq, "gemm_q norm only")
+    ms = (synth.bf16_bits_to_f32(got).astype(np.float64) ** 2).mean(axis=-1)
+    assert np.abs(ms - 1.0).max() < 2e-2                        # unit mean square up to bf16 rounding
+    # rotation without gain
+    got = _run_fused(X, W, None, None, 1e-5, cos, sin, None, B, L, C, H, D, bq)
+    ref, ref_bits = oracle.gemm_q(X, W, None, None, bq, H, D, eps=float(np.float32(1e-5)), rope_cos=cos, rope_sin=sin)
+    _check(got, ref, ref_bits, None, bq, "gemm_q norm + rope, no gain")
+
+
+def test_fused_norm_rope_full_width_sampled():
+    """Channel count of the video workload (3072 -> 24 heads x 128), 1024 tokens."""
+    print("[case] gemm_q norm+rope C=3072", flush=True)
+    B, L, C, H, D, bq = 1, 1024, 3072, 24, 128, 128
+    X, W, b, flags = _case(51, B, L, C, H, D, bq, cached=0.5)
+    g = synth.f32_to_bf16_bits((1.0 + 0.2 * np.random.default_rng(52).standard_normal(D)).astype(np.float32))
+    cos, sin = _rope_tables(L, D)
+    got = _run_fused(X, W, b, g, 1e-6, cos, sin, flags, B, L, C, H, D, bq)
+    ref, ref_bits = oracle.gemm_q(X, W, b, flags, bq, H, D, norm_weight=g, eps=float(np.float32(1e-6)), rope_cos=cos, rope_sin=sin)
+    _check(got, ref, ref_bits, flags, bq, "gemm_q norm+rope C=3072")
