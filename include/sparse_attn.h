@@ -111,6 +111,29 @@ int sparse_gemm_q_stream(const void* X, const void* W, const void* bias, const u
                          int B, int L, int C, int H, int D, int block_q, void* hip_stream);
 
 /*
+ * Reusable plan (Section 3.2: symbols are refreshed at an Update step and then drive the following Dispatch
+ * steps unchanged; Section 3.3: one symbol may cover n x n tiles).  sparse_attn_plan_create runs the
+ * symbol pre-pass once -- decode of S_c and S_s, kept-pair counts, the ordered work list -- and keeps its
+ * result on the device; sparse_attn_plan_run is sparse_attn_fwd_stream without that pre-pass.
+ *   cache_flags  device, uint8 [B, H, ceil(Tq / granularity)] or NULL
+ *   kv_mask      device, uint8 [B, H, ceil(Tq / granularity), ceil(ceil(Tkv / granularity) / 8)] or NULL, bit
+ *                order as for sparse_attn_fwd: tile (i, j) is computed iff bit (i / granularity, j / granularity)
+ *                is set, the decoding functions F and J of Section 3.4 with n = granularity
+ *   granularity  1..64; block_q x block_k stays the tile the kernel works on
+ * create allocates the plan's device buffer (hipMalloc) and enqueues the pre-pass on hip_stream; the symbol
+ * arrays may be changed or freed once that work has run.  The plan belongs to the device that was current at
+ * create.  run allocates nothing; it must be ordered after create (same stream, or synchronise), and two
+ * runs of one plan must not overlap in time (they share its queue counters).  destroy waits for the device
+ * and frees.  Errors as for sparse_attn_fwd; on failure *plan is NULL.
+ */
+typedef struct sparse_attn_plan sparse_attn_plan;
+int sparse_attn_plan_create(const uint8_t* cache_flags, const uint8_t* kv_mask, int B, int H, int L, int block_q,
+                            int block_k, int granularity, void* hip_stream, sparse_attn_plan** plan);
+int sparse_attn_plan_run(const sparse_attn_plan* plan, const void* Q, const void* K, const void* V, const void* O_cache,
+                         void* O, int D, void* hip_stream);
+int sparse_attn_plan_destroy(sparse_attn_plan* plan);
+
+/*
  * GEMM-Q with the two token-wise operations of Equation 2 fused into its epilogue:
  *     Q[b,h,token,:] = OP_RoPE(OP_RMSNorm(X[b,token,:] . W_h^T + bias_h))
  * for every (b,h,i) whose flag is clear (flagged tiles return at once, as in sparse_gemm_q).

@@ -20,6 +20,7 @@ from .symbols import update_symbols, compressed_map, caching_metrics  # noqa: F4
 from .reference import (  # noqa: F401
     pack_symbols,
     unpack_symbols,
+    expand_granularity,
     sparse_attention,
     sparse_attention_blocks,
     count_pairs,

@@ -69,6 +69,15 @@ def unpack_symbols(symbols, n):
     return out
 
 
+def expand_granularity(cache_flags, M_s, n, Tq, Tkv):
+    """Symbols at granularity n (one entry per n x n tiles, Section 3.3) -> one entry per tile, following the
+    decoding functions of Section 3.4: tile (i, j) reads flag i // n and mask entry (i // n, j // n).
+    cache_flags: [B,H,ceil(Tq/n)] or None; M_s: logical [B,H,ceil(Tq/n),ceil(Tkv/n)] or None."""
+    f = None if cache_flags is None else np.repeat(np.asarray(cache_flags), n, axis=2)[:, :, :Tq]
+    m = None if M_s is None else np.repeat(np.repeat(np.asarray(M_s), n, axis=2), n, axis=3)[:, :, :Tq, :Tkv]
+    return f, m
+
+
 def _u16(a, name):
     a = np.ascontiguousarray(a)
     if a.dtype != np.uint16:

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     sparse_attn_fwd_timed,
     sparse_gemm_q,
     sparse_gemm_o,
+    SparseAttnPlan,
     sparse_gemm_q_norm_rope,
     sparse_symbols_update,
     sparse_attn_fwd_forecast,

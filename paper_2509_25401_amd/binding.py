@@ -52,6 +52,12 @@ def load_library():
     lib.sparse_gemm_q.restype = i32
     lib.sparse_gemm_q_stream.argtypes = [vp] * 5 + [i32] * 6 + [vp]
     lib.sparse_gemm_q_stream.restype = i32
+    lib.sparse_attn_plan_create.argtypes = [vp, vp] + [i32] * 6 + [vp, ctypes.POINTER(vp)]
+    lib.sparse_attn_plan_create.restype = i32
+    lib.sparse_attn_plan_run.argtypes = [vp] * 6 + [i32, vp]
+    lib.sparse_attn_plan_run.restype = i32
+    lib.sparse_attn_plan_destroy.argtypes = [vp]
+    lib.sparse_attn_plan_destroy.restype = i32
     lib.sparse_gemm_q_norm_rope.argtypes = [vp] * 4 + [ctypes.c_float] + [vp] * 4 + [i32] * 6 + [vp]
     lib.sparse_gemm_q_norm_rope.restype = i32
     lib.sparse_gemm_o.argtypes = [vp] * 4 + [i32, vp, vp] + [i32] * 6
@@ -158,6 +164,44 @@ def sparse_gemm_q(X, W, bias, cache_flags, Q, block_q, stream=None):
     if rc != 0:
         _raise(rc)
     return Q
+
+
+class SparseAttnPlan:
+    """Handle of sparse_attn_plan_create: the symbol pre-pass stored for the Dispatch steps that reuse the symbols."""
+
+    def __init__(self, cache_flags, kv_mask, B, H, L, block_q, block_k, granularity=1, stream=None):
+        self._h = ctypes.c_void_p()
+        self.shape = (int(B), int(H), int(L))
+        rc = load_library().sparse_attn_plan_create(_dev_ptr(cache_flags, "cache_flags", True),
+                                                    _dev_ptr(kv_mask, "kv_mask", True), int(B), int(H), int(L),
+                                                    int(block_q), int(block_k), int(granularity), _stream_ptr(stream),
+                                                    ctypes.byref(self._h))
+        if rc != 0:
+            _raise(rc)
+
+    def run(self, Q, K, V, O_cache, O, stream=None):
+        B, H, L, D = Q.shape
+        if (B, H, L) != self.shape:
+            raise ValueError("Q does not have the shape the plan was made for")
+        rc = load_library().sparse_attn_plan_run(self._h, _dev_ptr(Q, "Q"), _dev_ptr(K, "K"), _dev_ptr(V, "V"),
+                                                 _dev_ptr(O_cache, "O_cache", True), _dev_ptr(O, "O"), int(D),
+                                                 _stream_ptr(stream))
+        if rc != 0:
+            _raise(rc)
+        return O
+
+    def destroy(self):
+        if self._h:
+            rc = load_library().sparse_attn_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+            if rc != 0:
+                _raise(rc)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
 
 
 def sparse_gemm_q_norm_rope(X, W, bias, norm_weight, eps, rope_cos, rope_sin, cache_flags, Q, block_q, stream=None):

@@ -27,6 +27,7 @@
 
 #include <map>
 #include <mutex>
+#include <new>
 #include <type_traits>
 #include <utility>
 
@@ -85,24 +86,32 @@ struct AttnParams {
 // Symbol pre-pass
 // ---------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) plan_rows(const uint8_t* __restrict__ cache_flags,
-                                                 const uint8_t* __restrict__ kv_mask, int N, int Tkv,
-                                                 int row_bytes, int nw32, uint32_t* __restrict__ words,
-                                                 int32_t* __restrict__ keys) {
+                                                 const uint8_t* __restrict__ kv_mask, int N, int Tq, int Tkv,
+                                                 int gran, int sym_Tq, int sym_row_bytes, int nw32,
+                                                 uint32_t* __restrict__ words, int32_t* __restrict__ keys) {
   const int row = blockIdx.x * blockDim.x + threadIdx.x;
   if (row >= N) return;
-  const bool cached = cache_flags != nullptr && cache_flags[row] != 0;
+  // one symbol covers gran x gran tiles: tile (i, j) reads flag i / gran and mask bit (i / gran, j / gran)
+  const int bh = row / Tq;
+  const size_t sym_row = (size_t)bh * sym_Tq + (row - bh * Tq) / gran;
+  const bool cached = cache_flags != nullptr && cache_flags[sym_row] != 0;
   int count = 0;
-  const uint8_t* src = kv_mask ? kv_mask + (size_t)row * row_bytes : nullptr;
+  const uint8_t* src = kv_mask ? kv_mask + sym_row * sym_row_bytes : nullptr;
   for (int w = 0; w < nw32; ++w) {
     uint32_t word = 0;
     if (!cached) {
-      if (src) {
+      if (!src) {
+        word = 0xffffffffu;
+      } else if (gran == 1) {
         for (int b = 0; b < 4; ++b) {
           const int byte = 4 * w + b;
-          if (byte < row_bytes) word |= (__brev((uint32_t)src[byte]) >> 24) << (8 * b);
+          if (byte < sym_row_bytes) word |= (__brev((uint32_t)src[byte]) >> 24) << (8 * b);
         }
       } else {
-        word = 0xffffffffu;
+        for (int t = 0; t < 32 && 32 * w + t < Tkv; ++t) {
+          const int js = (32 * w + t) / gran;
+          word |= (uint32_t)((src[js >> 3] >> (7 - (js & 7))) & 1) << t;
+        }
       }
       const int valid = Tkv - 32 * w;   // >= 1 by construction of nw32
       if (valid < 32) word &= (1u << valid) - 1u;
@@ -111,6 +120,11 @@ __global__ void __launch_bounds__(256) plan_rows(const uint8_t* __restrict__ cac
     count += __popc(word);
   }
   keys[row] = cached ? -1 : count;
+}
+
+// Copies the initial queue heads and ends of a stored plan into the live ones its next run consumes.
+__global__ void reset_queues(const uint32_t* __restrict__ init, uint32_t* __restrict__ live) {
+  if (threadIdx.x < 2 * kXcds) live[threadIdx.x] = init[threadIdx.x];
 }
 
 // Work list order: one queue per XCD (head bh belongs to XCD bh % kXcds, so the workgroups of
@@ -626,6 +640,56 @@ int launch_attn(const AttnParams& p, int grid, hipStream_t stream) {
   return 0;
 }
 
+struct PlanBuffers {
+  uint32_t* queues;   // kXcds live queue heads, then kXcds queue ends
+  uint32_t* order;    // [N]
+  int32_t* keys;      // [N]
+  uint32_t* words;    // [N][nw32]
+};
+
+PlanBuffers carve(char* base, const Shape& s) {
+  PlanBuffers b;
+  b.queues = (uint32_t*)base;
+  b.order = (uint32_t*)(base + 256);
+  b.keys = (int32_t*)(base + 256 + align256((size_t)s.N * 4));
+  b.words = (uint32_t*)(base + 256 + 2 * align256((size_t)s.N * 4));
+  return b;
+}
+
+}  // namespace
+
+// A stored pre-pass: decoded symbol words and the ordered work list of one set of symbols.
+struct sparse_attn_plan {
+  Shape s;
+  int gran;
+  int dev;
+  void* mem;               // [initial queue heads and ends (256 B)] [workspace as carved above]
+  uint32_t* queues_init;
+  PlanBuffers bufs;
+};
+
+namespace {
+
+// Enqueues the symbol pre-pass: decode + count per row, then the ordered work list; the queue heads and
+// ends go to `queues_out`.
+int launch_plan(const uint8_t* cache_flags, const uint8_t* kv_mask, const Shape& s, int gran, const PlanBuffers& pb,
+                uint32_t* queues_out, hipStream_t stream) {
+  const int BH = s.B * s.H;
+  const int heads_per_xcd = (BH + kXcds - 1) / kXcds;
+  int shift = 0;
+  while (((heads_per_xcd - 1) >> shift) + 1 > kMaxHeadGroups) ++shift;
+  const int groups = ((heads_per_xcd - 1) >> shift) + 1;
+  const int sym_Tq = (s.Tq + gran - 1) / gran;
+  const int sym_row_bytes = ((s.Tkv + gran - 1) / gran + 7) / 8;
+  hipLaunchKernelGGL(plan_rows, dim3((s.N + 255) / 256), dim3(256), 0, stream, cache_flags, kv_mask, s.N, s.Tq, s.Tkv,
+                     gran, sym_Tq, sym_row_bytes, s.nw32, pb.words, pb.keys);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(plan_order, dim3(1), dim3(kOrderThreads), 0, stream, pb.keys, s.N, s.Tq, s.Tkv, shift, groups,
+                     pb.order, queues_out);
+  HIP_TRY(hipGetLastError());
+  return 0;
+}
+
 struct Forecast {
   const void* const* terms;   // host array of n device pointers
   const float* coef;          // host array of n weights
@@ -634,7 +698,7 @@ struct Forecast {
 
 int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags, const uint8_t* kv_mask,
         const void* O_cache, void* O, int B, int H, int L, int D, int bq, int bk, hipStream_t stream, float* plan_ms,
-        float* attn_ms, bool timed, const Forecast* fc = nullptr) {
+        float* attn_ms, bool timed, const Forecast* fc = nullptr, const sparse_attn_plan* plan = nullptr) {
   Shape s;
   if (int rc = check_shape(B, H, L, D, bq, bk, true, &s)) return rc;
   if (!Q || !K || !V || !O) return fail(SPARSE_ATTN_ERR_INVALID, "Q, K, V and O must not be NULL");
@@ -658,16 +722,18 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
     }
   }
 
-  void* ws = nullptr;
-  if (int rc = sa_get_scratch(workspace_bytes(s), stream, &ws)) return rc;
-  char* base = (char*)ws;
-  uint32_t* queues = (uint32_t*)base;
-  uint32_t* order = (uint32_t*)(base + 256);
-  int32_t* keys = (int32_t*)(base + 256 + align256((size_t)s.N * 4));
-  uint32_t* words = (uint32_t*)(base + 256 + 2 * align256((size_t)s.N * 4));
+  PlanBuffers pb;
+  if (plan) {
+    pb = plan->bufs;
+  } else {
+    void* ws = nullptr;
+    if (int rc = sa_get_scratch(workspace_bytes(s), stream, &ws)) return rc;
+    pb = carve((char*)ws, s);
+  }
 
   int dev = 0, cus = 0;
   HIP_TRY(hipGetDevice(&dev));
+  if (plan && dev != plan->dev) return fail(SPARSE_ATTN_ERR_INVALID, "the plan was created on device %d, current device is %d", plan->dev, dev);
   HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
 
   hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
@@ -684,19 +750,17 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
   }
   if (record) HIP_TRY(hipEventRecord(ev[0], stream));
 
-  const int BH = B * H;
-  const int heads_per_xcd = (BH + kXcds - 1) / kXcds;
-  int shift = 0;
-  while (((heads_per_xcd - 1) >> shift) + 1 > kMaxHeadGroups) ++shift;
-  const int groups = ((heads_per_xcd - 1) >> shift) + 1;
-  hipLaunchKernelGGL(plan_rows, dim3((s.N + 255) / 256), dim3(256), 0, stream, cache_flags, kv_mask, s.N, s.Tkv,
-                     s.row_bytes, s.nw32, words, keys);
-  HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(plan_order, dim3(1), dim3(kOrderThreads), 0, stream, keys, s.N, s.Tq, s.Tkv, shift, groups,
-                     order, queues);
-  HIP_TRY(hipGetLastError());
+  if (plan) {
+    hipLaunchKernelGGL(reset_queues, dim3(1), dim3(64), 0, stream, plan->queues_init, pb.queues);
+    HIP_TRY(hipGetLastError());
+  } else {
+    if (int rc = launch_plan(cache_flags, kv_mask, s, 1, pb, pb.queues, stream)) return rc;
+  }
   if (record) HIP_TRY(hipEventRecord(ev[1], stream));
 
+  uint32_t* const queues = pb.queues;
+  uint32_t* const order = pb.order;
+  uint32_t* const words = pb.words;
   AttnParams p;
   p.Q = (const char*)Q;
   p.K = (const char*)K;
@@ -783,6 +847,52 @@ int sparse_attn_fwd_forecast(const void* Q, const void* K, const void* V, const 
   const Forecast fc = {O_terms, coef, n_terms};
   return run(Q, K, V, cache_flags, kv_mask, nullptr, O, B, H, L, D, block_q, block_k, (hipStream_t)hip_stream, nullptr,
              nullptr, false, &fc);
+}
+
+int sparse_attn_plan_create(const uint8_t* cache_flags, const uint8_t* kv_mask, int B, int H, int L, int block_q,
+                            int block_k, int granularity, void* hip_stream, sparse_attn_plan** plan_out) {
+  if (!plan_out) return fail(SPARSE_ATTN_ERR_INVALID, "plan_out must not be NULL");
+  *plan_out = nullptr;
+  Shape s;
+  if (int rc = check_shape(B, H, L, 0, block_q, block_k, false, &s)) return rc;
+  if (granularity < 1 || granularity > 64)
+    return fail(SPARSE_ATTN_ERR_INVALID, "granularity=%d must be between 1 and 64", granularity);
+  sparse_attn_plan* pl = new (std::nothrow) sparse_attn_plan();
+  if (!pl) return fail(SPARSE_ATTN_ERR_HIP, "out of host memory");
+  pl->s = s;
+  pl->gran = granularity;
+  pl->mem = nullptr;
+  hipError_t e = hipGetDevice(&pl->dev);
+  if (e == hipSuccess) e = hipMalloc(&pl->mem, 256 + workspace_bytes(s));
+  if (e != hipSuccess) {
+    delete pl;
+    return fail(SPARSE_ATTN_ERR_HIP, "plan allocation failed: %s", hipGetErrorString(e));
+  }
+  pl->queues_init = (uint32_t*)pl->mem;
+  pl->bufs = carve((char*)pl->mem + 256, s);
+  if (int rc = launch_plan(cache_flags, kv_mask, s, granularity, pl->bufs, pl->queues_init, (hipStream_t)hip_stream)) {
+    (void)hipFree(pl->mem);
+    delete pl;
+    return rc;
+  }
+  *plan_out = pl;
+  return 0;
+}
+
+int sparse_attn_plan_run(const sparse_attn_plan* plan, const void* Q, const void* K, const void* V, const void* O_cache,
+                         void* O, int D, void* hip_stream) {
+  if (!plan) return fail(SPARSE_ATTN_ERR_INVALID, "plan must not be NULL");
+  const Shape& s = plan->s;
+  return run(Q, K, V, nullptr, nullptr, O_cache, O, s.B, s.H, s.L, D, s.bq, s.bk, (hipStream_t)hip_stream, nullptr,
+             nullptr, false, nullptr, plan);
+}
+
+int sparse_attn_plan_destroy(sparse_attn_plan* plan) {
+  if (!plan) return 0;
+  const hipError_t e = hipFree(plan->mem);     // waits for work that still uses the buffer
+  delete plan;
+  if (e != hipSuccess) return fail(SPARSE_ATTN_ERR_HIP, "hipFree failed: %s", hipGetErrorString(e));
+  return 0;
 }
 
 size_t sparse_attn_workspace_bytes(int B, int H, int L, int block_q, int block_k) {

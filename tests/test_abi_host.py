@@ -222,3 +222,17 @@ def _gemm_q_nr(eps=1e-6, cos=ctypes.c_void_p(0x50000000), sin=ctypes.c_void_p(0x
 def test_gemm_q_norm_rope_argument_validation_precedes_any_device_work(kw, code):
     assert _gemm_q_nr(**kw) == code
     assert pkg.sparse_attn_last_error() != ""
+
+
+def test_plan_create_validation_precedes_any_device_work():
+    lib = pkg.load_library()
+    h = ctypes.c_void_p(0x1234)
+    for kw, code in ((dict(L=100), -1), (dict(bq=32), -2), (dict(g=0), -1), (dict(g=65), -1), (dict(B=0), -1)):
+        a = dict(B=1, H=1, L=256, bq=128, bk=128, g=1)
+        a.update(kw)
+        assert lib.sparse_attn_plan_create(None, None, a["B"], a["H"], a["L"], a["bq"], a["bk"], a["g"], None, ctypes.byref(h)) == code
+        assert h.value is None and pkg.sparse_attn_last_error() != ""
+        h = ctypes.c_void_p(0x1234)
+    assert lib.sparse_attn_plan_create(None, None, 1, 1, 256, 128, 128, 1, None, None) == -1
+    assert lib.sparse_attn_plan_run(None, FAKE, FAKE, FAKE, None, FAKE, 128, None) == -1
+    assert lib.sparse_attn_plan_destroy(None) == 0

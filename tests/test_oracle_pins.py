@@ -270,3 +270,21 @@ def test_pair_accounting_matches_plain_counting():
     assert oracle.sparsity(w.cache_flags, mask, w.B, w.H, w.L, 48, 16) == pytest.approx(1 - brute / total)
     k2, _ = oracle.count_pairs(None, None, w.B, w.H, w.L, 48, 16)
     assert k2 == total
+
+
+def test_granularity_expansion_follows_the_decoding_functions():
+    """Section 3.4: F(S_c, i) reads entry i/n, J(S_s, i, j) reads entry (i/n)(T_kv/n) + j/n of the flat stream."""
+    rng = np.random.default_rng(77)
+    n, Tq, Tkv = 3, 7, 8
+    sq, sk = -(-Tq // n), -(-Tkv // n)
+    flags = (rng.random((2, 2, sq)) < 0.5).astype(np.uint8)
+    M = (rng.random((2, 2, sq, sk)) < 0.5).astype(np.uint8)
+    f, m = oracle.expand_granularity(flags, M, n, Tq, Tkv)
+    assert f.shape == (2, 2, Tq) and m.shape == (2, 2, Tq, Tkv)
+    flat = M.reshape(2, 2, -1)
+    for i in range(Tq):
+        assert (f[:, :, i] == flags[:, :, i // n]).all()
+        for j in range(Tkv):
+            assert (m[:, :, i, j] == flat[:, :, (i // n) * sk + j // n]).all()
+    f1, m1 = oracle.expand_granularity(flags, M, 1, sq, sk)
+    assert (f1 == flags).all() and (m1 == M).all()
