@@ -158,6 +158,34 @@ def main():
         del Oc, fl4, mk4
         Q.copy_(up_bf16(w.Q)); K.copy_(up_bf16(w.K)); V.copy_(up_bf16(w.V))
     if not args.no_extras:
+        # 2K-image shape (17K tokens: 128 x 128 patches + 512 text tokens), dense and at 25 % keep, through a stored plan
+        L17, T17 = 16896, 132
+        g17 = torch.Generator(device=dev); g17.manual_seed(17)
+        q17, k17, v17 = (torch.randn((1, H, L17, w.D), device=dev, generator=g17).to(torch.bfloat16) for _ in range(3))
+        o17 = torch.empty_like(q17)
+        rng17 = np.random.default_rng(np.random.SeedSequence([synth.BASE_SEED + 17]))
+        M17 = synth.video_sweep_mask(rng17, 1, H, T17, 4, 0.25, False)
+        res17 = {}
+        for label, M in (("dense", None), ("keep25", M17)):
+            mk = None if M is None else up_u8(pkg.sparse_attn_pack_mask(M))
+            plan = pkg.SparseAttnPlan(None, mk, 1, H, L17, w.block_q, w.block_k)
+            for _ in range(2):
+                plan.run(q17, k17, v17, None, o17)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(few):
+                plan.run(q17, k17, v17, None, o17)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t) / few * 1e3
+            kept = H * T17 * T17 if M is None else int(M.sum())
+            res17[label] = dict(ms_per_step=ms, keep=kept / (H * T17 * T17), eff_tflops=flop_per_pair * kept / ms / 1e9)
+            plan.destroy()
+        res17["speedup_vs_dense"] = res17["dense"]["ms_per_step"] / res17["keep25"]["ms_per_step"]
+        extra["image_17k_tokens"] = res17
+        log(f"17K tokens (2K image), stored plan: dense {res17['dense']['ms_per_step']:.3f} ms ({res17['dense']['eff_tflops']:.0f} TFLOP/s), "
+            f"keep {res17['keep25']['keep']:.3f}: {res17['keep25']['ms_per_step']:.3f} ms ({res17['keep25']['eff_tflops']:.0f} TFLOP/s), "
+            f"{res17['speedup_vs_dense']:.2f}x")
+        del q17, k17, v17, o17
         # the step before attention (GEMM-Q, Section 3.5): 3072 channels -> 24 heads x 128, flags skip tiles
         C = 3072
         g = torch.Generator(device=dev); g.manual_seed(7)

@@ -57,6 +57,7 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
   constexpr int X_INST = X_TILEB / 1024;
   constexpr int W_LOAD = (W_INST + NWAVES - 1) / NWAVES;
   constexpr int X_LOAD = (X_INST + NWAVES - 1) / NWAVES;
+  constexpr int TS = D / 2 + 2;            // padded row of the cos / sin tiles in LDS (floats)
   static_assert(W_INST % NWAVES == 0 && X_INST % NWAVES == 0, "stage loads must split evenly over the waves");
 
   // tile of this workgroup: head fastest, so the 8 XCDs (workgroup n runs on XCD n mod 8) each keep
@@ -187,6 +188,25 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
             acc[a][1][4 * q4 + e] += bv;
           }
     }
+    // The tile's cos / sin rows (one contiguous block of the tables) come through LDS: read straight
+    // from memory in the accumulator layout, every lane would fetch 8 bytes from its own 256-byte row,
+    // 64 dependent round trips per lane.  The operand stages are dead by now; rows are padded by two
+    // floats so that 32 lanes reading 8 bytes of 32 rows hit 64 different banks.
+    __syncthreads();                           // every wave is done reading the operand stages
+    float* tab = (float*)smem;                 // cos [BQ][TS], then sin [BQ][TS], then the sums [WN][BQ]
+    if (p.rope_cos) {
+      constexpr int NV = BQ * (D / 2) / 4;     // 16-byte pieces per table
+      const float4* gc = (const float4*)(p.rope_cos + (size_t)i * BQ * (D / 2));
+      const float4* gs = (const float4*)(p.rope_sin + (size_t)i * BQ * (D / 2));
+      for (int e = tid; e < NV; e += NWAVES * 64) {
+        const float4 vc = gc[e], vs = gs[e];
+        const int o = (4 * e) / (D / 2) * TS + (4 * e) % (D / 2);
+        *(float2*)(tab + o) = make_float2(vc.x, vc.y);
+        *(float2*)(tab + o + 2) = make_float2(vc.z, vc.w);
+        *(float2*)(tab + BQ * TS + o) = make_float2(vs.x, vs.y);
+        *(float2*)(tab + BQ * TS + o + 2) = make_float2(vs.z, vs.w);
+      }
+    }
     float ss[2];
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
@@ -197,14 +217,13 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
         for (int e = 0; e < 16; ++e) v = fmaf(acc[a][c][e], acc[a][c][e], v);
       ss[c] = v + __shfl_xor(v, 32);
     }
+    float* part = tab + 2 * BQ * TS;           // [WN][BQ]
+    if (WN == 2 && half == 0) {
+      part[wn * BQ + wm * 64 + l32] = ss[0];
+      part[wn * BQ + wm * 64 + 32 + l32] = ss[1];
+    }
+    __syncthreads();                           // tables and partial sums are in place
     if constexpr (WN == 2) {
-      __syncthreads();                         // every wave is done reading the operand stages
-      float* part = (float*)smem;              // [wn][BQ]
-      if (half == 0) {
-        part[wn * BQ + wm * 64 + l32] = ss[0];
-        part[wn * BQ + wm * 64 + 32 + l32] = ss[1];
-      }
-      __syncthreads();
       ss[0] = part[wm * 64 + l32] + part[BQ + wm * 64 + l32];
       ss[1] = part[wm * 64 + 32 + l32] + part[BQ + wm * 64 + 32 + l32];
     }
@@ -238,9 +257,10 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
           for (int e = 0; e < 4; ++e) y[e] = y[e] * inv_rms[c] * gain[e];
           if (p.rope_cos) {
             // channels d0..d0+3 are the pairs d0/2 and d0/2 + 1 of this token
-            const size_t at = ((size_t)i * BQ + wm * 64 + 32 * c + l32) * (D / 2) + d0 / 2;
-            const float2 cs = *(const float2*)(p.rope_cos + at);
-            const float2 sn = *(const float2*)(p.rope_sin + at);
+            const float* tab = (const float*)smem;
+            const int at = (wm * 64 + 32 * c + l32) * TS + d0 / 2;
+            const float2 cs = *(const float2*)(tab + at);
+            const float2 sn = *(const float2*)(tab + BQ * TS + at);
             const float y0 = y[0] * cs.x - y[1] * sn.x, y1 = y[0] * sn.x + y[1] * cs.x;
             const float y2 = y[2] * cs.y - y[3] * sn.y, y3 = y[2] * sn.y + y[3] * cs.y;
             y[0] = y0; y[1] = y1; y[2] = y2; y[3] = y3;
@@ -261,7 +281,9 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
 
 template <int BQ, int D, bool NORM_ROPE>
 int launch(const GemmQParams& p, int tiles, hipStream_t stream) {
-  constexpr size_t lds = 2 * (size_t)(D + BQ) * kRowB;
+  constexpr size_t stage_lds = 2 * (size_t)(D + BQ) * kRowB;
+  constexpr size_t epi_lds = NORM_ROPE ? (size_t)(2 * BQ * (D / 2 + 2) + 2 * BQ) * 4 : 0;   // cos, sin tiles + row sums
+  constexpr size_t lds = stage_lds > epi_lds ? stage_lds : epi_lds;
   constexpr int threads = (BQ / 64) * (D / 64) * 64;
   static bool attr_set = false;
   if (!attr_set) {
