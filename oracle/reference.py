@@ -102,9 +102,7 @@ def _check(Q, K, V, cache_flags, kv_mask, O_cache, block_q, block_k):
     B, H, L, D = Q.shape
     if K.shape != Q.shape or V.shape != Q.shape:
         raise ValueError("Q, K, V must share the shape [B, H, L, D]")
-    if L % block_q or L % block_k:
-        raise ValueError("L must be a multiple of both block sizes")
-    Tq, Tkv = L // block_q, L // block_k
+    Tq, Tkv = -(-L // block_q), -(-L // block_k)      # Definition 1: ceil(L / b) blocks, the last may be short
     if cache_flags is not None and cache_flags.shape != (B, H, Tq):
         raise ValueError("cache_flags must be [B, H, Tq]")
     if kv_mask is not None and kv_mask.shape != (B, H, Tq, (Tkv + 7) // 8):

@@ -74,16 +74,18 @@ int oracle_mask_row_bytes(int Tkv)
  * One query block of one head.  Kd, Vd: that head's keys/values widened to double,
  * [L][D].  Qh: that head's bf16 queries [L][D].  mask_row: packed symbols of this
  * (b,h,i) or NULL for "all kept".  out: [bq][D] doubles.  scores: scratch of L doubles.
+ * Definition 1 counts ceil(L / b) blocks: the last query block and the last key block may be
+ * short; rows of `out` past the end of the sequence are left untouched.
  */
 static void compute_block(const uint16_t *Qh, const double *Kd, const double *Vd,
                           const uint8_t *mask_row, int i, int L, int D, int bq, int bk,
                           double *out, double *scores)
 {
-    const int Tkv = L / bk;
+    const int Tkv = (L + bk - 1) / bk;
     const double inv_sqrt_d = 1.0 / sqrt((double)D);
     double *q = (double *)malloc((size_t)D * sizeof(double));
 
-    for (int r = 0; r < bq; ++r) {
+    for (int r = 0; r < bq && i * bq + r < L; ++r) {
         const uint16_t *qrow = Qh + ((size_t)i * bq + r) * D;
         double *orow = out + (size_t)r * D;
         for (int c = 0; c < D; ++c) {
@@ -98,7 +100,7 @@ static void compute_block(const uint16_t *Qh, const double *Kd, const double *Vd
             if (mask_row && !symbol_bit(mask_row, j))
                 continue;
             any = 1;
-            for (int k = j * bk; k < (j + 1) * bk; ++k) {
+            for (int k = j * bk; k < (j + 1) * bk && k < L; ++k) {
                 const double *krow = Kd + (size_t)k * D;
                 double dot = 0.0;
                 for (int c = 0; c < D; ++c)
@@ -117,7 +119,7 @@ static void compute_block(const uint16_t *Qh, const double *Kd, const double *Vd
         for (int j = 0; j < Tkv; ++j) {
             if (mask_row && !symbol_bit(mask_row, j))
                 continue;
-            for (int k = j * bk; k < (j + 1) * bk; ++k) {
+            for (int k = j * bk; k < (j + 1) * bk && k < L; ++k) {
                 double p = exp(scores[k] - m);
                 const double *vrow = Vd + (size_t)k * D;
                 l += p;
@@ -153,9 +155,7 @@ int oracle_sparse_attn_blocks(const uint16_t *Q, const uint16_t *K, const uint16
 {
     if (!Q || !K || !V || !O_f64 || B <= 0 || H <= 0 || L <= 0 || D <= 0 || bq <= 0 || bk <= 0)
         return -1;
-    if (L % bq || L % bk)
-        return -1;
-    const int Tq = L / bq, Tkv = L / bk;
+    const int Tq = (L + bq - 1) / bq, Tkv = (L + bk - 1) / bk;
     const int row_bytes = oracle_mask_row_bytes(Tkv);
     const size_t head_elems = (size_t)L * D;
     const size_t blk_elems = (size_t)bq * D;
@@ -191,7 +191,8 @@ int oracle_sparse_attn_blocks(const uint16_t *Q, const uint16_t *K, const uint16
                 if (cache_flags && cache_flags[items[n]]) {
                     if (O_cache) {
                         const uint16_t *src = O_cache + bh * head_elems + (size_t)i * blk_elems;
-                        for (size_t t = 0; t < blk_elems; ++t) {
+                        const int rows = L - i * bq < bq ? L - i * bq : bq;
+                        for (size_t t = 0; t < (size_t)rows * D; ++t) {
                             out[t] = widen_bf16(src[t]);
                             if (outb)
                                 outb[t] = src[t];
@@ -201,9 +202,11 @@ int oracle_sparse_attn_blocks(const uint16_t *Q, const uint16_t *K, const uint16
                 }
                 const uint8_t *mrow = kv_mask ? kv_mask + (size_t)items[n] * row_bytes : NULL;
                 compute_block(Q + bh * head_elems, Kd, Vd, mrow, i, L, D, bq, bk, out, scores);
-                if (outb)
-                    for (size_t t = 0; t < blk_elems; ++t)
+                if (outb) {
+                    const int rows = L - i * bq < bq ? L - i * bq : bq;
+                    for (size_t t = 0; t < (size_t)rows * D; ++t)
                         outb[t] = narrow_bf16(out[t]);
+                }
             }
             free(scores);
         }
@@ -219,16 +222,57 @@ int oracle_sparse_attn(const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                        const uint16_t *O_cache, int B, int H, int L, int D, int bq, int bk,
                        double *O_f64, uint16_t *O_bits)
 {
-    if (B <= 0 || H <= 0 || L <= 0 || bq <= 0 || L % bq)
+    if (B <= 0 || H <= 0 || L <= 0 || bq <= 0)
         return -1;
-    const int64_t n = (int64_t)B * H * (L / bq);
+    const int Tq = (L + bq - 1) / bq;
+    const int64_t n = (int64_t)B * H * Tq;
     int64_t *items = (int64_t *)malloc((size_t)n * sizeof(int64_t));
     if (!items)
         return -1;
     for (int64_t t = 0; t < n; ++t)
         items[t] = t;
-    int rc = oracle_sparse_attn_blocks(Q, K, V, cache_flags, kv_mask, O_cache, B, H, L, D, bq, bk,
+    int rc = 0;
+    if (L % bq == 0) {
+        /* the blocks of [n][bq][D] are the rows of [B][H][L][D] in order */
+        rc = oracle_sparse_attn_blocks(Q, K, V, cache_flags, kv_mask, O_cache, B, H, L, D, bq, bk,
                                        items, n, O_f64, O_bits);
+    } else {
+        /* short last block: go through [n][bq][D] staging arrays, seeded with what O holds so that
+         * "left untouched" keeps its meaning, and copy the rows that exist back */
+        const size_t blk = (size_t)bq * D;
+        double *tf = (double *)calloc((size_t)n * blk, sizeof(double));
+        uint16_t *tb = (uint16_t *)calloc((size_t)n * blk, sizeof(uint16_t));
+        if (!tf || !tb) {
+            free(tf);
+            free(tb);
+            free(items);
+            return -1;
+        }
+        for (int pass = 0; pass < 2; ++pass) {
+            if (pass == 1)
+                rc = oracle_sparse_attn_blocks(Q, K, V, cache_flags, kv_mask, O_cache, B, H, L, D, bq,
+                                               bk, items, n, tf, O_bits ? tb : NULL);
+            for (int64_t t = 0; t < n; ++t) {
+                const int64_t bh = t / Tq;
+                const int i = (int)(t % Tq);
+                const int rows = L - i * bq < bq ? L - i * bq : bq;
+                const size_t at = ((size_t)bh * L + (size_t)i * bq) * D;
+                for (size_t e = 0; e < (size_t)rows * D; ++e) {
+                    if (pass == 0) {
+                        tf[(size_t)t * blk + e] = O_f64[at + e];
+                        if (O_bits)
+                            tb[(size_t)t * blk + e] = O_bits[at + e];
+                    } else {
+                        O_f64[at + e] = tf[(size_t)t * blk + e];
+                        if (O_bits)
+                            O_bits[at + e] = tb[(size_t)t * blk + e];
+                    }
+                }
+            }
+        }
+        free(tf);
+        free(tb);
+    }
     free(items);
     return rc;
 }
@@ -241,9 +285,9 @@ int oracle_sparse_attn(const uint16_t *Q, const uint16_t *K, const uint16_t *V,
 int oracle_count_pairs(const uint8_t *cache_flags, const uint8_t *kv_mask, int B, int H,
                        int L, int bq, int bk, int64_t *kept, int64_t *total)
 {
-    if (B <= 0 || H <= 0 || L <= 0 || bq <= 0 || bk <= 0 || L % bq || L % bk)
+    if (B <= 0 || H <= 0 || L <= 0 || bq <= 0 || bk <= 0)
         return -1;
-    const int Tq = L / bq, Tkv = L / bk;
+    const int Tq = (L + bq - 1) / bq, Tkv = (L + bk - 1) / bk;
     const int row_bytes = oracle_mask_row_bytes(Tkv);
     int64_t k = 0;
     for (int64_t row = 0; row < (int64_t)B * H * Tq; ++row) {

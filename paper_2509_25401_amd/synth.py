@@ -60,11 +60,11 @@ class Workload:
 
     @property
     def Tq(self):
-        return self.L // self.block_q
+        return -(-self.L // self.block_q)
 
     @property
     def Tkv(self):
-        return self.L // self.block_k
+        return -(-self.L // self.block_k)
 
     def kept_pairs(self) -> int:
         """Number of (q-block, kv-block) pairs that are computed (plain counting on the logical mask)."""
@@ -102,7 +102,7 @@ def random_case(seed, B, H, L, D, block_q, block_k, keep=0.5, cached_frac=0.0, n
                 force_diagonal=True, with_cache_tensor=None) -> Workload:
     """Generic small case: i.i.d. Bernoulli(keep) mask (+ diagonal), random cached rows."""
     r = [np.random.default_rng(s) for s in np.random.SeedSequence(seed).spawn(6)]
-    Tq, Tkv = L // block_q, L // block_k
+    Tq, Tkv = -(-L // block_q), -(-L // block_k)      # a short last block counts as a block
     with_cache = cached_frac > 0 if with_cache_tensor is None else with_cache_tensor
     Q, K, V, Oc = _qkv(r, B, H, L, D, with_cache)
     M = r[4].random((B, H, Tq, Tkv)) < keep

@@ -21,13 +21,13 @@ def brute_force_attention(Q, K, V, M_s, cache_flags, block_q, block_k):
     """
     Qf, Kf, Vf = bits_to_f64(Q), bits_to_f64(K), bits_to_f64(V)
     B, H, L, D = Qf.shape
-    Tq, Tkv = L // block_q, L // block_k
+    Tq = -(-L // block_q)
     out = np.empty((B, H, L, D), dtype=np.float64)
     for b in range(B):
         for h in range(H):
             S = Qf[b, h] @ Kf[b, h].T / np.sqrt(D)
             if M_s is not None:
-                elem = np.kron(np.asarray(M_s[b, h], dtype=bool), np.ones((block_q, block_k), dtype=bool))
+                elem = np.kron(np.asarray(M_s[b, h], dtype=bool), np.ones((block_q, block_k), dtype=bool))[:L, :L]
                 S = np.where(elem, S, -np.inf)
             empty = ~np.isfinite(S).any(axis=1)
             S[empty] = 0.0
@@ -46,4 +46,4 @@ def computed_row_mask(cache_flags, B, H, L, block_q):
     """bool [B,H,L]: True for rows that belong to computed (non-cached) blocks."""
     if cache_flags is None:
         return np.ones((B, H, L), dtype=bool)
-    return np.repeat(np.asarray(cache_flags) == 0, block_q, axis=2)
+    return np.repeat(np.asarray(cache_flags) == 0, block_q, axis=2)[:, :, :L]

@@ -288,3 +288,35 @@ def test_granularity_expansion_follows_the_decoding_functions():
             assert (m[:, :, i, j] == flat[:, :, (i // n) * sk + j // n]).all()
     f1, m1 = oracle.expand_granularity(flags, M, 1, sq, sk)
     assert (f1 == flags).all() and (m1 == M).all()
+
+
+# ---------------------------------------------------------------- short last blocks (Definition 1: ceil(L / b) blocks)
+@pytest.mark.parametrize("case", [
+    dict(B=1, H=2, L=100, D=16, bq=32, bk=32, keep=0.5, cached=0.0),     # 4 blocks, the last holds 4 rows / 4 keys
+    dict(B=2, H=1, L=77, D=8, bq=16, bk=32, keep=0.6, cached=0.3),       # different raggedness on the two axes
+    dict(B=1, H=1, L=130, D=32, bq=64, bk=16, keep=0.4, cached=0.4),
+    dict(B=1, H=2, L=33, D=8, bq=32, bk=32, keep=1.0, cached=0.0),       # one full block and one row / one key
+])
+def test_short_last_blocks_against_element_level_brute_force(case):
+    w = synth.random_case(300 + case["L"], case["B"], case["H"], case["L"], case["D"], case["bq"], case["bk"],
+                          keep=case["keep"], cached_frac=case["cached"], force_diagonal=False)
+    assert w.M_s.shape[-2:] == (-(-case["L"] // case["bq"]), -(-case["L"] // case["bk"]))
+    O, Ob = oracle.sparse_attention(w.Q, w.K, w.V, w.cache_flags, oracle.pack_symbols(w.M_s), w.O_cache, case["bq"], case["bk"])
+    ref = brute_force_attention(w.Q, w.K, w.V, w.M_s, w.cache_flags, case["bq"], case["bk"])
+    rows = computed_row_mask(w.cache_flags, w.B, w.H, w.L, w.block_q)
+    assert rows.any() and np.abs(O[rows] - ref[rows]).max() < 1e-12
+    if w.cache_flags is not None and (~rows).any():
+        assert (Ob[~rows] == w.O_cache[~rows]).all()
+
+
+def test_short_sequence_dense_is_textbook_attention_and_block_subsets_agree():
+    B, H, L, D, bq, bk = 1, 2, 150, 16, 64, 64
+    w = synth.random_case(12, B, H, L, D, bq, bk, keep=1.0)
+    O, _ = oracle.sparse_attention(w.Q, w.K, w.V, None, None, None, bq, bk)
+    q, k, v = (torch.from_numpy(bits_to_f64(t)) for t in (w.Q, w.K, w.V))
+    assert np.abs(O - torch.nn.functional.scaled_dot_product_attention(q, k, v).numpy()).max() < 1e-12
+    items = np.array([2, 5], dtype=np.int64)                   # the short last block of each head
+    blocks, _ = oracle.sparse_attention_blocks(w.Q, w.K, w.V, None, None, None, bq, bk, items)
+    assert np.abs(blocks[0, :22] - O[0, 0, 128:]).max() == 0 and np.abs(blocks[1, :22] - O[0, 1, 128:]).max() == 0
+    assert (blocks[:, 22:] == 0).all()                         # rows past the end are left alone
+    assert oracle.count_pairs(None, None, B, H, L, bq, bk) == (18, 18)
