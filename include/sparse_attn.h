@@ -26,8 +26,10 @@
  *   - Scores are scaled by 1 / sqrt(D) (Section 3.1).  Products run on bf16 MFMA with fp32
  *     accumulation, the softmax weights are rounded to bf16 before the PV product, the result
  *     is rounded to bf16 (nearest even).
- *   - Supported shapes: D in {64, 128}; block_q, block_k in {64, 128}; L a multiple of both
- *     block sizes; Tq <= 16384.
+ *   - Supported shapes: D in {64, 128}; block_q, block_k in {64, 128}; any L >= 1 with
+ *     Tq = ceil(L / block_q) <= 16384 and Tkv = ceil(L / block_k) (Definition 1): the last query
+ *     block and the last key block may be short; nothing past row L - 1 of a head is read or
+ *     written.  (The projections and the symbol generation below need L to be a multiple.)
  *   - "device" pointers are HIP device memory owned by the caller; the library never frees
  *     or keeps them.  "host" pointers are ordinary host memory.
  *   - Return value: 0 on success, a negative SPARSE_ATTN_ERR_* code otherwise; a message for
@@ -47,7 +49,7 @@ extern "C" {
 #endif
 
 #define SPARSE_ATTN_OK 0
-#define SPARSE_ATTN_ERR_INVALID (-1)     /* NULL pointer, non-positive size, L not a multiple of a block, O aliases an input */
+#define SPARSE_ATTN_ERR_INVALID (-1)     /* NULL pointer, non-positive size, a size that does not fit the others, O aliases an input */
 #define SPARSE_ATTN_ERR_UNSUPPORTED (-2) /* D or block size outside the supported set, Tq too large */
 #define SPARSE_ATTN_ERR_HIP (-3)         /* a HIP runtime call failed; see sparse_attn_last_error() */
 

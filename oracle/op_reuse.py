@@ -38,7 +38,7 @@ def attention_with_forecast(Q, K, V, cache_flags, kv_mask, terms, coef, block_q,
     O, O_bits = sparse_attention(Q, K, V, cache_flags, kv_mask, None, block_q, block_k)
     if cache_flags is not None:
         f, fb = op_reuse(terms, coef)
-        rows = np.repeat(np.asarray(cache_flags) != 0, block_q, axis=2)
+        rows = np.repeat(np.asarray(cache_flags) != 0, block_q, axis=2)[:, :, :O.shape[2]]
         O[rows] = f[rows]
         O_bits[rows] = fb[rows]
     return O, O_bits

@@ -200,7 +200,12 @@ __device__ __forceinline__ int v_swizzle(int row) {
   return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1);
 }
 
-template <int D, int BQ, int BK>
+// RAGGED: the sequence length is not a multiple of the blocks (Definition 1 counts ceil(L / b) of them).
+// The last query block then has fewer rows and the last key block fewer keys: loads of missing rows
+// re-read the last row that exists, scores of missing keys are set to -inf before the softmax, stores of
+// missing query rows are dropped, and a 64-key sub-tile that lies entirely past the end is not visited.
+// The aligned instantiation contains none of this.
+template <int D, int BQ, int BK, bool RAGGED>
 __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
   constexpr int NWAVES = BQ / 32;
   constexpr int NT = NWAVES * 64;
@@ -285,7 +290,8 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
 
     if (entry & kCopyFlag) {
       // cache-then-reuse: O_i <- cached O_i, bit exact
-      constexpr int NV = BQ * ROWB / 16;
+      int NV = BQ * ROWB / 16;
+      if constexpr (RAGGED) NV = min(BQ, p.L - iq * BQ) * (ROWB / 16);
       if (p.n_terms > 0) {
         // forecast: fp32 sum of the scaled terms in order, rounded once to bf16
         const bf16x8* t0 = (const bf16x8*)(p.O_cache + blk_off);
@@ -326,7 +332,9 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     // already the exponent of 2 and the softmax needs no multiply per score.
     bf16x8 qf[KS];
     {
-      const char* qrow = p.Q + blk_off + (size_t)(wave * 32 + l32) * ROWB + half * 16;
+      int qr = wave * 32 + l32;
+      if constexpr (RAGGED) qr = min(qr, p.L - 1 - iq * BQ);
+      const char* qrow = p.Q + blk_off + (size_t)qr * ROWB + half * 16;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const bf16x8 q = *(const bf16x8*)(qrow + ks * 32);
@@ -371,6 +379,21 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       const size_t tile_off = ((size_t)j * BK + (size_t)sub * kKeys) * ROWB;
       const char* gK = Kh + tile_off;
       const char* gV = Vh + tile_off;
+      if constexpr (RAGGED) {
+        const int valid = p.L - (j * BK + sub * kKeys);     // >= 1: sub-tiles past the end are never requested
+        if (valid < kKeys) {
+#pragma unroll
+          for (int t = 0; t < NLOAD; ++t) {
+            const int r = (wave + t * NWAVES) * ROWS_PER_INST + lane / CH;
+            const int pch = lane % CH;
+            const int src_row = min(r, valid - 1);            // LDS row r receives the last row that exists
+            const unsigned dst = (unsigned)(buf * TILEB + (wave + t * NWAVES) * 1024);
+            sa_load_to_lds_16B(gK, (unsigned)(src_row * ROWB + ((pch ^ k_swizzle<D>(r)) * 16)), lds_base + dst);
+            sa_load_to_lds_16B(gV, (unsigned)(src_row * ROWB + ((pch ^ v_swizzle<D>(r)) * 16)), lds_base + 2 * TILEB + dst);
+          }
+          return;
+        }
+      }
 #pragma unroll
       for (int t = 0; t < NLOAD; ++t) {
         const unsigned dst = (unsigned)(buf * TILEB + (wave + t * NWAVES) * 1024);
@@ -379,7 +402,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       }
     };
 
-    auto compute = [&](auto buf_c) {
+    auto compute = [&](auto buf_c, int valid) {   // valid: keys of this sub-tile that exist (RAGGED only)
       // the buffer index is a compile-time constant, so every LDS address below is a per-lane
       // register that never changes plus an immediate offset
       constexpr int buf = decltype(buf_c)::value;
@@ -407,6 +430,16 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
         s[t / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t], qf[t % KS], t % KS == 0 ? neg_ref : s[t / KS], 0, 0, 0);
       }
       __builtin_amdgcn_s_setprio(0);
+      if constexpr (RAGGED) {
+        if (valid < kKeys) {
+          // accumulator register e of block kb2 is key 32*kb2 + 8*(e/4) + 4*half + e%4 of the sub-tile
+          const int lim = valid - 4 * half;
+#pragma unroll
+          for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[kb2][e] = (32 * kb2 + 8 * (e / 4) + e % 4 >= lim) ? -INFINITY : s[kb2][e];
+        }
+      }
       // first operands of the O^T product: fetched now, consumed after the softmax
       bf16x8 va[NPV];
 #pragma unroll
@@ -480,6 +513,9 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     if (j >= 0) issue_loads(j, 0, Buf0{});
     auto step = [&](auto cur, auto other) {
       int nj = j, nsub = sub + 1;
+      if constexpr (RAGGED) {
+        if (nsub < SUB && j * BK + nsub * kKeys >= p.L) nsub = SUB;   // the rest of the last block does not exist
+      }
       if (nsub == SUB) {
         nsub = 0;
         nj = next_block();
@@ -487,7 +523,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       sa_wait_vmem();
       __syncthreads();   // this sub-tile has landed for every wave; the other buffer is free
       if (nj >= 0) issue_loads(nj, nsub, other);
-      compute(cur);
+      compute(cur, RAGGED ? p.L - (j * BK + sub * kKeys) : kKeys);
       j = nj;
       sub = nsub;
     };
@@ -504,6 +540,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       const float l_tot = __builtin_bit_cast(float, (unsigned)sw[0]) + __builtin_bit_cast(float, (unsigned)sw[1]);
       const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
       char* orow = p.O + blk_off + (size_t)(wave * 32 + l32) * ROWB;
+      const bool row_exists = !RAGGED || iq * BQ + wave * 32 + l32 < p.L;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -517,7 +554,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
           u32x2 pk;
           pk[0] = __builtin_bit_cast(unsigned, lo);
           pk[1] = __builtin_bit_cast(unsigned, hi);
-          *(u32x2*)(orow + (32 * db + 8 * q4 + 4 * half) * 2) = pk;
+          if (row_exists) *(u32x2*)(orow + (32 * db + 8 * q4 + 4 * half) * 2) = pk;
         }
     }
     __syncthreads();
@@ -560,14 +597,13 @@ int check_shape(int B, int H, int L, int D, int bq, int bk, bool need_d, Shape* 
   if ((bq != 64 && bq != 128) || (bk != 64 && bk != 128))
     return fail(SPARSE_ATTN_ERR_UNSUPPORTED, "block_q and block_k must be 64 or 128 (got %d, %d)", bq, bk);
   if (need_d && D != 64 && D != 128) return fail(SPARSE_ATTN_ERR_UNSUPPORTED, "D must be 64 or 128 (got %d)", D);
-  if (L % bq || L % bk)
-    return fail(SPARSE_ATTN_ERR_INVALID, "L=%d must be a multiple of block_q=%d and block_k=%d", L, bq, bk);
-  const long long n = (long long)B * H * (L / bq);
-  if (L / bq > kMaxTq) return fail(SPARSE_ATTN_ERR_UNSUPPORTED, "Tq=%d exceeds %d", L / bq, kMaxTq);
+  const int tq = (L + bq - 1) / bq;      // a short last block counts as a block
+  const long long n = (long long)B * H * tq;
+  if (tq > kMaxTq) return fail(SPARSE_ATTN_ERR_UNSUPPORTED, "Tq=%d exceeds %d", tq, kMaxTq);
   if (n > 0x3fffffffLL) return fail(SPARSE_ATTN_ERR_UNSUPPORTED, "too many query blocks (%lld)", n);
   s->B = B; s->H = H; s->L = L; s->D = D; s->bq = bq; s->bk = bk;
-  s->Tq = L / bq;
-  s->Tkv = L / bk;
+  s->Tq = tq;
+  s->Tkv = (L + bk - 1) / bk;
   s->N = (int)n;
   s->row_bytes = (s->Tkv + 7) / 8;
   s->nw32 = (s->Tkv + 31) / 32;
@@ -626,18 +662,24 @@ bool overlaps(const void* a, const void* b, size_t bytes) {
   return x < y + bytes && y < x + bytes;
 }
 
-template <int D, int BQ, int BK>
-int launch_attn(const AttnParams& p, int grid, hipStream_t stream) {
+template <int D, int BQ, int BK, bool RAGGED>
+int launch_attn_variant(const AttnParams& p, int grid, hipStream_t stream) {
   constexpr size_t lds = 4 * (size_t)kKeys * D * 2 + 16;
   static bool attr_set = false;
   if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute((const void*)attn_kernel<D, BQ, BK>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds));
+    HIP_TRY(hipFuncSetAttribute((const void*)attn_kernel<D, BQ, BK, RAGGED>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((attn_kernel<D, BQ, BK>), dim3(grid), dim3(BQ * 2), lds, stream, p);
+  hipLaunchKernelGGL((attn_kernel<D, BQ, BK, RAGGED>), dim3(grid), dim3(BQ * 2), lds, stream, p);
   HIP_TRY(hipGetLastError());
   return 0;
+}
+
+template <int D, int BQ, int BK>
+int launch_attn(const AttnParams& p, int grid, hipStream_t stream) {
+  if (p.L % BQ || p.L % BK) return launch_attn_variant<D, BQ, BK, true>(p, grid, stream);
+  return launch_attn_variant<D, BQ, BK, false>(p, grid, stream);
 }
 
 struct PlanBuffers {

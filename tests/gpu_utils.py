@@ -60,7 +60,7 @@ def oracle_full(w):
 def cached_rows(w):
     if w.cache_flags is None:
         return np.zeros((w.B, w.H, w.L), dtype=bool)
-    return np.repeat(np.asarray(w.cache_flags) != 0, w.block_q, axis=2)
+    return np.repeat(np.asarray(w.cache_flags) != 0, w.block_q, axis=2)[:, :, :w.L]
 
 
 def check_against_oracle(w, got_bits, ref_f64, ref_bits, label=""):

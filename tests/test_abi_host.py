@@ -44,8 +44,6 @@ def _fwd(B=1, H=1, L=128, D=128, bq=128, bk=128, Q=FAKE, K=FAKE, V=FAKE, O=ctype
 
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), -1), (dict(H=-1), -1), (dict(L=0), -1), (dict(D=0), -1),
-    (dict(L=192), -1),                 # not a multiple of the 128 blocks
-    (dict(L=192, bq=64, bk=128), -1),
     (dict(D=96), -2), (dict(D=256), -2),
     (dict(bq=32), -2), (dict(bk=256), -2), (dict(bq=0), -1),
     (dict(Q=None), -1), (dict(K=None), -1), (dict(V=None), -1), (dict(O=None), -1),
@@ -62,7 +60,7 @@ def test_argument_validation_precedes_any_device_work(kw, code):
 def test_workspace_bytes():
     assert pkg.sparse_attn_workspace_bytes(1, 24, 33024, 128, 128) >= 24 * 258 * (4 + 4 + 9 * 4)
     assert pkg.sparse_attn_workspace_bytes(1, 24, 33024, 128, 128) < 1 << 20
-    assert pkg.sparse_attn_workspace_bytes(1, 1, 100, 128, 128) == 0
+    assert pkg.sparse_attn_workspace_bytes(1, 1, 100, 128, 128) == pkg.sparse_attn_workspace_bytes(1, 1, 128, 128, 128) > 0
     assert pkg.sparse_attn_workspace_bytes(1, 1, 128, 32, 128) == 0
 
 
@@ -83,8 +81,10 @@ def test_count_kept_matches_oracle_accounting():
         assert pkg.sparse_attn_count_kept(w.cache_flags, m, w.B, w.H, w.L, 128, 64) == \
             oracle.count_pairs(w.cache_flags, mask, w.B, w.H, w.L, 128, 64) == (w.kept_pairs(), w.total_pairs())
     assert pkg.sparse_attn_count_kept(None, None, w.B, w.H, w.L, 128, 64) == (w.total_pairs(), w.total_pairs())
+    # a short last block counts as a block (Definition 1): 100 tokens = 1 query block x 2 key blocks
+    assert pkg.sparse_attn_count_kept(None, None, 1, 1, 100, 128, 64) == oracle.count_pairs(None, None, 1, 1, 100, 128, 64) == (2, 2)
     with pytest.raises(pkg.SparseAttnError):
-        pkg.sparse_attn_count_kept(None, None, 1, 1, 100, 128, 64)
+        pkg.sparse_attn_count_kept(None, None, 1, 1, 100, 32, 64)
 
 
 def test_workload_recipes_hit_their_keep_ratios():
@@ -193,7 +193,7 @@ def _forecast(n_terms=2, terms=(0x30000000, 0x40000000), coef=(1.0, 2.0), O=ctyp
     (dict(terms=(0x30000000, None)), -1), (dict(terms=(0x30000004, 0x40000000)), -1),
     (dict(terms=(0x30000000, 0x90000000)), -1),            # a term overlaps O
     (dict(coef=(1.0, float("nan"))), -1),
-    (dict(L=100), -1), (dict(D=96), -2),
+    (dict(L=0), -1), (dict(D=96), -2),
 ])
 def test_forecast_argument_validation_precedes_any_device_work(kw, code):
     assert _forecast(**kw) == code
@@ -227,7 +227,7 @@ def test_gemm_q_norm_rope_argument_validation_precedes_any_device_work(kw, code)
 def test_plan_create_validation_precedes_any_device_work():
     lib = pkg.load_library()
     h = ctypes.c_void_p(0x1234)
-    for kw, code in ((dict(L=100), -1), (dict(bq=32), -2), (dict(g=0), -1), (dict(g=65), -1), (dict(B=0), -1)):
+    for kw, code in ((dict(L=0), -1), (dict(bq=32), -2), (dict(g=0), -1), (dict(g=65), -1), (dict(B=0), -1)):
         a = dict(B=1, H=1, L=256, bq=128, bk=128, g=1)
         a.update(kw)
         assert lib.sparse_attn_plan_create(None, None, a["B"], a["H"], a["L"], a["bq"], a["bk"], a["g"], None, ctypes.byref(h)) == code
