@@ -16,8 +16,10 @@
 //               each lane owns one query row: the row maximum needs a single half-wave exchange,
 //               the row sum none until the end, and the exponentiated S^T accumulators are the
 //               B operand of the O^T product without any data movement.  The reference of the
-//               exponent is the C operand of the first S^T MFMA and moves only when a score
-//               exceeds it by 2^8.  A copy item moves one cached block O_cache -> O.
+//               exponent is the C operand of the first S^T MFMA; it is checked after the fact
+//               (the sum of a sub-tile's weights shows whether a score left the allowed range)
+//               and moves only then, so the steady state takes no row maximum at all.  A copy
+//               item moves one cached block O_cache -> O.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdarg.h>
@@ -57,7 +59,7 @@ constexpr int kHwRegXccId = (3 << 11) | 20;   // s_getreg operand: 4 bits at off
 constexpr int kOrderThreads = 1024;
 constexpr int kMaxTerms = 4;            // stored feature + up to three derivatives
 constexpr int kMfmaPrio = 1;            // wave priority while it feeds the matrix pipe
-constexpr float kRescaleLog2 = 8.0f;    // how far (log2) a score may exceed the exponent's reference before it moves
+constexpr float kSumLimit = 256.0f;     // a lane's 32 weights of one sub-tile may add up to this before the reference moves
 
 struct AttnParams {
   const char* Q;
@@ -351,9 +353,9 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     // Reference of the exponent (log2 domain) of this lane's query row, kept NEGATED in all 16
     // registers of an accumulator: it is the C operand of the first MFMA of every S^T block, so
     // the MFMA delivers score - reference and the softmax needs no subtraction per score either.
-    // The reference is not the running maximum: it is raised only when a score exceeds it by
-    // more than kRescaleLog2 (weights stay below 2^kRescaleLog2); the final division by the
-    // row sum cancels it exactly.
+    // The reference is not the running maximum: it is raised (to the row maximum seen so far) only
+    // when the weights of a sub-tile show that a score left the allowed range above it; the final
+    // division by the row sum cancels it exactly.
     f32x16 neg_ref;
 #pragma unroll
     for (int e = 0; e < 16; ++e) neg_ref[e] = 0.f;
@@ -445,18 +447,47 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
 #pragma unroll
       for (int t = 0; t < kPre; ++t) va[t] = v_read(t);
 
-      // this lane sees 32 of the 64 scores of its query row; the other half sits in lane ^ 32
-      float mx = s[0][0];
+      // Weights, rounded to bf16 for the O^T product; the row sum adds up the same rounded values.
+      // k-slot s of lane-half h of the O^T MFMA maps to key 32*kb2 + 16*ksp + 8*(s/4) + 4*h + s%4,
+      // which is exactly the key order of the S^T accumulator registers 8*ksp .. 8*ksp+7.
+      // The exponent's reference is checked after the fact: the weights are formed against the current
+      // reference straight away, and only if their sum shows that one of them left the allowed range
+      // (or on the first sub-tile, which has no reference yet) is the row maximum taken, the reference
+      // moved, and the weights formed again.  In the common case the softmax costs no maximum at all.
+      bf16x8 pb[4];
+      bf16x2 ones;
+      ones[0] = (__bf16)1.0f;
+      ones[1] = (__bf16)1.0f;
+      float dl = 0.f;
+      auto weights = [&]() {
+        dl = 0.f;
 #pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2)
+        for (int g = 0; g < 4; ++g) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb2][e]);
-      {
-        const unsigned bits = __builtin_bit_cast(unsigned, mx);
-        const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
-        mx = fmaxf(__builtin_bit_cast(float, (unsigned)sw[0]), __builtin_bit_cast(float, (unsigned)sw[1]));
-      }
-      if (first || __builtin_amdgcn_ballot_w64(mx > kRescaleLog2) != 0) {
+          for (int e = 0; e < 8; ++e) pb[g][e] = (__bf16)__builtin_amdgcn_exp2f(s[g >> 1][8 * (g & 1) + e]);
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            bf16x2 pr;
+            pr[0] = pb[g][e];
+            pr[1] = pb[g][e + 1];
+            dl = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, dl, false);
+          }
+        }
+      };
+      if (!first) weights();
+      // !(dl <= limit) also catches an overflowed (infinite or NaN) sum
+      if (first || __builtin_amdgcn_ballot_w64(!(dl <= kSumLimit)) != 0) {
+        // this lane sees 32 of the 64 scores of its query row; the other half sits in lane ^ 32
+        float mx = s[0][0];
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb2][e]);
+        {
+          const unsigned bits = __builtin_bit_cast(unsigned, mx);
+          const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+          mx = fmaxf(__builtin_bit_cast(float, (unsigned)sw[0]), __builtin_bit_cast(float, (unsigned)sw[1]));
+        }
         // move the reference: to the row maximum on the first sub-tile, upwards only afterwards
         const float d = first ? mx : fmaxf(mx, 0.f);
 #pragma unroll
@@ -475,26 +506,9 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) neg_ref[e] = nr;
         first = false;
+        weights();
       }
-      // weights, rounded to bf16 for the O^T product; the row sum adds up the same rounded values.
-      // k-slot s of lane-half h of the O^T MFMA maps to key 32*kb2 + 16*ksp + 8*(s/4) + 4*h + s%4,
-      // which is exactly the key order of the S^T accumulator registers 8*ksp .. 8*ksp+7.
-      bf16x8 pb[4];
-      bf16x2 ones;
-      ones[0] = (__bf16)1.0f;
-      ones[1] = (__bf16)1.0f;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pb[g][e] = (__bf16)__builtin_amdgcn_exp2f(s[g >> 1][8 * (g & 1) + e]);
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-          bf16x2 pr;
-          pr[0] = pb[g][e];
-          pr[1] = pb[g][e + 1];
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_run, false);
-        }
-      }
+      l_run += dl;
       __builtin_amdgcn_s_setprio(kMfmaPrio);
 #pragma unroll
       for (int t = 0; t < NPV; ++t) {
