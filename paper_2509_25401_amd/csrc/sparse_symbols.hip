@@ -16,11 +16,14 @@
 //                 ascending cumulative sums of C and of G both stay <= tau_c times the totals; text
 //                 blocks are never cached; if the share of blocks left to compute drops below S_q,
 //                 every block of the head is cached.
-// The cumulative sums need no sort: entry v adds up every entry that is smaller, or equal with a
-// smaller-or-same index, T^2 compare-and-adds per row with T a few hundred.
+// Neither rule needs a sort.  Equation 1 (once per head): entry v adds up every entry that is smaller, or equal with
+// a smaller-or-same index.  The skipping rule (once per map row): the skipped set is "everything up to a threshold
+// value", found by bisection on the bits of that value.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "sparse_attn.h"
 #include "sparse_attn_internal.h"
@@ -29,7 +32,6 @@ namespace {
 
 constexpr int kMapRows = 8;          // map rows per workgroup (two per wave)
 constexpr int kChunk = 32;           // pooled key rows staged in LDS per step
-constexpr int kCoopTail = 12;        // a last pass with fewer entries than this is done entry by entry
 constexpr int kMaxBlocks = 2048;     // blocks per sequence the LDS arrays are sized for
 
 __device__ __forceinline__ float wave_max(float v) {
@@ -38,6 +40,30 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 __device__ __forceinline__ float wave_sum(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// Sum over the 64 lanes, the same bits in every lane, without going through LDS: exchanges inside a row of 16
+// lanes are DPP operands of the add, the two exchanges between rows are the gfx950 lane-swap instructions.
+// Every step adds a value and its mirror partner's, so both partners compute the same sum.
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  auto dpp = [](float x, auto ctrl) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, 0xf, 0xf, true));
+  };
+  v += dpp(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]: lane ^ 1
+  v += dpp(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]: lane ^ 2
+  v += dpp(v, std::integral_constant<int, 0x141>{});   // row_half_mirror: the other quad of each 8 lanes
+  v += dpp(v, std::integral_constant<int, 0x140>{});   // row_mirror: the other 8 lanes of each row
+  {
+    const unsigned bits = __float_as_uint(v);
+    const auto sw = __builtin_amdgcn_permlane16_swap(bits, bits, false, false);   // rows 0<->1, 2<->3
+    v = __uint_as_float((unsigned)sw[0]) + __uint_as_float((unsigned)sw[1]);
+  }
+  {
+    const unsigned bits = __float_as_uint(v);
+    const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);   // lanes 0-31 <-> 32-63
+    v = __uint_as_float((unsigned)sw[0]) + __uint_as_float((unsigned)sw[1]);
+  }
   return v;
 }
 
@@ -86,46 +112,63 @@ __global__ void __launch_bounds__(256) pool_blocks(const uint16_t* __restrict__ 
   }
 }
 
-// Entry t of a row's ascending cumulative sum: every entry that is smaller, or equal with index <= t.
-// Entries before the 64 that this pass of the wave owns have a smaller index than all of them (so "<="
-// decides), entries after them a larger one ("<" decides); only the 64 in between need the index.
-// `pr` is padded to a multiple of 4 entries with +inf, which no comparison ever selects.
-// Two rows (pa, pb) are walked together so that their independent compare / select / add chains interleave.
-__device__ __forceinline__ void cumsum_up_at2(const float* pa, const float* pb, int T_pad, int j0, int j, float aj,
-                                              float bj, float& cs_a, float& cs_b) {
-  float ca = 0.f, cb = 0.f;
-  int k = 0;
-  for (; k < j0; k += 4) {
-    const float4 a = *(const float4*)&pa[k], b = *(const float4*)&pb[k];
-    ca += a.x <= aj ? a.x : 0.f;
-    cb += b.x <= bj ? b.x : 0.f;
-    ca += a.y <= aj ? a.y : 0.f;
-    cb += b.y <= bj ? b.y : 0.f;
-    ca += a.z <= aj ? a.z : 0.f;
-    cb += b.z <= bj ? b.z : 0.f;
-    ca += a.w <= aj ? a.w : 0.f;
-    cb += b.w <= bj ? b.w : 0.f;
+// The skipping rule without a sort.  "Skip block j iff the ascending cumulative sum at j is <= tau" selects a prefix
+// of the ascending order, i.e. all entries up to some value theta (plus, among entries equal to the next value,
+// the first few in index order).  S(x) = sum of the entries <= x is a non-decreasing step function of x (also as
+// computed here in fp32: a fixed summation structure is monotone in every term), so the largest float theta with
+// S(theta) <= tau is found by fixing its bits from the top: 30 wave-wide conditional sums per row instead of one
+// per entry.  Entries lie in (0, 1], so bit 29 is the highest that can be set.  Two rows (pa, pb) are searched
+// together so that their reductions overlap.  s_* returns S(theta_*).
+__device__ __forceinline__ void find_thresholds2(const float* pa, const float* pb, int T, int lane, float tau,
+                                                 float& theta_a, float& theta_b, float& s_a, float& s_b) {
+  unsigned lo_a = 0u, lo_b = 0u;
+  float sa = 0.f, sb = 0.f;
+  for (int bit = 29; bit >= 0; --bit) {
+    const float ca = __uint_as_float(lo_a | (1u << bit)), cb = __uint_as_float(lo_b | (1u << bit));
+    float xa = 0.f, xb = 0.f;
+    for (int k = lane; k < T; k += 64) {
+      const float a = pa[k], b = pb[k];
+      xa += a <= ca ? a : 0.f;
+      xb += b <= cb ? b : 0.f;
+    }
+    xa = wave_sum_dpp(xa);   // the same sum in every lane
+    xb = wave_sum_dpp(xb);
+    if (xa <= tau) {
+      lo_a |= 1u << bit;
+      sa = xa;
+    }
+    if (xb <= tau) {
+      lo_b |= 1u << bit;
+      sb = xb;
+    }
   }
-  const int mid_end = min(j0 + 64, T_pad);
-  for (; k < mid_end; ++k) {
-    const float a = pa[k], b = pb[k];
-    const bool first = k <= j;
-    ca += ((a < aj) | ((a == aj) & first)) ? a : 0.f;      // bitwise on purpose: no branches
-    cb += ((b < bj) | ((b == bj) & first)) ? b : 0.f;
+  theta_a = __uint_as_float(lo_a);
+  theta_b = __uint_as_float(lo_b);
+  s_a = sa;
+  s_b = sb;
+}
+
+// Entries equal to the smallest value above theta come next in the ascending order, in index order: how many of
+// them still fit under tau when added one by one to S(theta).  (With distinct values: none, by the choice of theta.)
+__device__ __forceinline__ void next_value_ties(const float* pr, int T, int lane, float theta, float s_theta, float tau,
+                                                float& next, int& n_skip) {
+  float nx = INFINITY;
+  for (int k = lane; k < T; k += 64) {
+    const float a = pr[k];
+    nx = fminf(nx, a > theta ? a : INFINITY);
   }
-  for (; k < T_pad; k += 4) {
-    const float4 a = *(const float4*)&pa[k], b = *(const float4*)&pb[k];
-    ca += a.x < aj ? a.x : 0.f;
-    cb += b.x < bj ? b.x : 0.f;
-    ca += a.y < aj ? a.y : 0.f;
-    cb += b.y < bj ? b.y : 0.f;
-    ca += a.z < aj ? a.z : 0.f;
-    cb += b.z < bj ? b.z : 0.f;
-    ca += a.w < aj ? a.w : 0.f;
-    cb += b.w < bj ? b.w : 0.f;
+  for (int o = 32; o > 0; o >>= 1) nx = fminf(nx, __shfl_xor(nx, o));
+  int m = 0;
+  for (int k0 = 0; k0 < T; k0 += 64) m += __popcll(__ballot(k0 + lane < T && pr[min(k0 + lane, T - 1)] == nx));
+  int n = 0;
+  float run = s_theta;
+  while (n < m) {
+    run += nx;
+    if (!(run <= tau)) break;
+    ++n;
   }
-  cs_a = ca;
-  cs_b = cb;
+  next = nx;
+  n_skip = n;
 }
 
 // Dynamic LDS: pooled query rows [kMapRows][D], one stage of pooled key rows [kChunk][D + 4] (padded so
@@ -155,14 +198,27 @@ __global__ void __launch_bounds__(256) map_rows(const float* __restrict__ pooled
   // (key tid % kChunk, row tid / kChunk) then takes one dot product
   static_assert(256 / kChunk == kMapRows, "one thread per (staged key, row)");
   const int jj = tid % kChunk, r = tid / kChunk;
-  for (int j0 = 0; j0 < T; j0 += kChunk) {
-    __syncthreads();
+  constexpr int NPF = kChunk * (D / 4) / 256;          // 16-byte pieces of a key stage per thread
+  float4 pre[NPF];                                     // the next stage, in flight while this one is used
+  auto fetch = [&](int j0) {
     const int nk = min(kChunk, T - j0);
-    for (int e = tid; e < nk * (D / 4); e += 256) {
-      const int kr = e / (D / 4), c = e % (D / 4);
-      *(float4*)&kst[kr * KS + 4 * c] = *(const float4*)&kt[(size_t)(j0 + kr) * D + 4 * c];
+#pragma unroll
+    for (int u = 0; u < NPF; ++u) {
+      const int e = tid + u * 256;
+      pre[u] = e < nk * (D / 4) ? *(const float4*)&kt[(size_t)j0 * D + 4 * e] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  fetch(0);
+  for (int j0 = 0; j0 < T; j0 += kChunk) {
+    __syncthreads();                                   // the previous stage has been consumed
+    const int nk = min(kChunk, T - j0);
+#pragma unroll
+    for (int u = 0; u < NPF; ++u) {
+      const int e = tid + u * 256;
+      *(float4*)&kst[(e / (D / 4)) * KS + 4 * (e % (D / 4))] = pre[u];
     }
     __syncthreads();
+    if (j0 + kChunk < T) fetch(j0 + kChunk);
     if (jj < nk) {
       const float4* kr = (const float4*)(kst + jj * KS);
       const float4* qr = (const float4*)(q + r * D);
@@ -205,33 +261,23 @@ __global__ void __launch_bounds__(256) map_rows(const float* __restrict__ pooled
   const float* pa = p + (2 * w) * T_pad;
   const float* pb = pa + T_pad;
   const int ia = i0 + 2 * w, ib = ia + 1;
+  float theta_a, theta_b, s_a, s_b, next_a, next_b;
+  int nskip_a, nskip_b;
+  find_thresholds2(pa, pb, T, lane, tau_kv, theta_a, theta_b, s_a, s_b);
+  next_value_ties(pa, T, lane, theta_a, s_a, tau_kv, next_a, nskip_a);
+  next_value_ties(pb, T, lane, theta_b, s_b, tau_kv, next_b, nskip_b);
+  const unsigned long long below = (1ull << lane) - 1ull;
+  int seen_a = 0, seen_b = 0;                                 // entries equal to next_* at smaller indices
   for (int j0 = 0; j0 < T; j0 += 64) {
-    unsigned long long kept_a = 0, kept_b = 0;              // bit l = key block j0 + l is kept
-    const int rem = T - j0;
-    if (rem >= kCoopTail) {
-      // every lane owns one entry of each row and walks over all others
-      const int j = j0 + lane;
-      const float aj = j < T ? pa[j] : 0.f, bj = j < T ? pb[j] : 0.f;
-      float cs_a, cs_b;
-      cumsum_up_at2(pa, pb, T_pad, j0, j, aj, bj, cs_a, cs_b);
-      kept_a = __ballot(j < T && cs_a > tau_kv);
-      kept_b = __ballot(j < T && cs_b > tau_kv);
-    } else {
-      // a short ragged tail: the whole wave works on one entry at a time instead of idling most lanes
-      for (int t = 0; t < rem; ++t) {
-        const int j = j0 + t;
-        const float aj = pa[j], bj = pb[j];
-        float part_a = 0.f, part_b = 0.f;
-        for (int k = lane; k < T; k += 64) {
-          const float a = pa[k], b = pb[k];
-          const bool first = k <= j;
-          part_a += ((a < aj) | ((a == aj) & first)) ? a : 0.f;
-          part_b += ((b < bj) | ((b == bj) & first)) ? b : 0.f;
-        }
-        if (wave_sum(part_a) > tau_kv) kept_a |= 1ull << t;   // the butterfly leaves the same sum in every lane
-        if (wave_sum(part_b) > tau_kv) kept_b |= 1ull << t;
-      }
-    }
+    const int j = j0 + lane;
+    const bool in = j < T;
+    const float a = in ? pa[j] : INFINITY, b = in ? pb[j] : INFINITY;
+    const unsigned long long tie_a = __ballot(a == next_a), tie_b = __ballot(b == next_b);
+    const bool skip_a = a <= theta_a || (a == next_a && seen_a + __popcll(tie_a & below) < nskip_a);
+    const bool skip_b = b <= theta_b || (b == next_b && seen_b + __popcll(tie_b & below) < nskip_b);
+    seen_a += __popcll(tie_a);
+    seen_b += __popcll(tie_b);
+    const unsigned long long kept_a = __ballot(in && !skip_a), kept_b = __ballot(in && !skip_b);   // bit l = block j0 + l
     // lanes 0-7 write the bytes of row a, lanes 8-15 those of row b; first block of a byte = bit 7
     const int byte = j0 / 8 + (lane & 7);
     const int i = lane < 8 ? ia : ib;
