@@ -248,3 +248,36 @@ def test_score_ranges_that_force_the_exponent_reference_to_move(profile):
     got = synth.bf16_bits_to_f32(DeviceCase(w).run())
     assert np.isfinite(got).all(), f"{profile}: non-finite output"
     assert np.abs(got - row).max() <= 2.0 ** -7 * np.abs(row).max() + 1e-6, f"{profile}: weights do not sum to one"
+
+
+def test_more_heads_than_the_order_pass_has_bins():
+    """640 (batch, head) pairs: 80 per XCD queue, more than the 64 head groups of the ordering pass, so heads are
+    grouped in pairs there; every block must still be computed exactly once."""
+    w = synth.random_case(synth.BASE_SEED + 310, 8, 80, 256, 64, 128, 64, keep=0.6, cached_frac=0.25)
+    got = DeviceCase(w).run()
+    ref, ref_bits = oracle_full(w)
+    check_against_oracle(w, got, ref, ref_bits, "640 heads")
+
+
+def test_long_sequence_many_symbol_words_sampled_blocks():
+    """3000 blocks of 64 tokens in one head: 94 symbol words per row, 375 mask bytes; sampled query blocks."""
+    B, H, L, D, bq, bk = 1, 1, 192000, 64, 64, 64
+    rng = np.random.default_rng(synth.BASE_SEED + 320)
+    w = synth.random_case(synth.BASE_SEED + 321, B, H, L, D, bq, bk, keep=0.02, force_diagonal=True)
+    T = L // bq
+    flags = (rng.random((B, H, T)) < 0.1).astype(np.uint8)
+    w.cache_flags = flags
+    w.O_cache = synth.normal_bf16(rng, w.Q.shape)
+    got = DeviceCase(w).run()
+    items = np.unique(np.concatenate([[0, 1, T - 2, T - 1], rng.integers(0, T, size=28)])).astype(np.int64)
+    ref, ref_bits = oracle.sparse_attention_blocks(w.Q, w.K, w.V, flags, oracle.pack_symbols(w.M_s), w.O_cache, bq, bk, items)
+    worst = 0.0
+    for n, i in enumerate(items):
+        rows = slice(i * bq, (i + 1) * bq)
+        if flags[0, 0, i]:
+            assert (got[0, 0, rows] == w.O_cache[0, 0, rows]).all()
+        else:
+            err = np.abs(synth.bf16_bits_to_f32(got[0, 0, rows]).astype(np.float64) - ref[n])
+            worst = max(worst, err.max())
+            assert err.max() <= 1e-2 and err.mean() <= 1e-3
+    print(f"[parity] 192000 tokens, {len(items)} sampled blocks: max-abs {worst:.3e}", flush=True)
