@@ -6,14 +6,15 @@
  * level sparse symbols (Definitions 1 and 2, Section 3.3):
  *   - a per (batch, head, query block) cache flag, the spatial-axis symbol S_c: a flagged
  *     block is not computed, its output is reused from a cached output tensor
- *     ("cache-then-reuse" with OP_reuse = identity, a bit-exact copy);
+ *     ("cache-then-reuse"; OP_reuse is the identity, a bit-exact copy, in sparse_attn_fwd
+ *     and a Taylor-series forecast in sparse_attn_fwd_forecast);
  *   - a bit-packed per (batch, head, query block, key block) mask, the reduction-axis symbol
  *     S_s: a pair whose bit is 0 is skipped, its K/V tile is never loaded, and the softmax
  *     normalises over the kept key blocks only ("compute-on-demand").
  *
  * Conventions shared by every entry point
  *   - Tensors Q, K, V, O_cache, O: bf16, shape [B, H, L, D], D fastest, fully contiguous,
- *     16-byte aligned base.  Tq = L / block_q, Tkv = L / block_k.
+ *     16-byte aligned base.  Tq = ceil(L / block_q), Tkv = ceil(L / block_k).
  *   - cache_flags: uint8 [B, H, Tq]; non-zero = reuse the block from O_cache.  Note the
  *     polarity: the paper's logical mask M_c holds 0 for cached blocks, this flag holds 1.
  *     NULL = no block is cached.
