@@ -39,8 +39,8 @@ def log(msg):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--keep", type=float, default=0.25, help="keep ratio of the headline mask")
     ap.add_argument("--no-extras", action="store_true", help="skip the dense run, the sweep and config 4")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -302,6 +302,15 @@ def main():
         log(f"symbols_update: {ms:.3f} ms ({extra['symbols_update']['gbps']:.0f} GB/s on Q+K), cached {extra['symbols_update']['cached_frac']:.2f}, "
             f"kept pairs {keep_frac:.2f}")
         del Qs, Ks, fl, mk
+    if not args.no_extras:
+        # what this device sustains on MFMAs alone (its clock under matrix load depends on the operand data)
+        tf_c, mhz_c = pkg.sparse_attn_probe_mfma(False)
+        tf_r, mhz_r = pkg.sparse_attn_probe_mfma(True)
+        extra["mfma_only"] = dict(constant_operands_tflops=tf_c, constant_operands_mhz=mhz_c,
+                                  random_operands_tflops=tf_r, random_operands_mhz=mhz_r,
+                                  attn_kernel_frac_of_random_operand_rate=head["kernel_tflops"] / tf_r)
+        log(f"MFMA-only loop: {tf_c:.0f} TFLOP/s at {mhz_c:.0f} MHz with constant operands, {tf_r:.0f} TFLOP/s at {mhz_r:.0f} MHz "
+            f"with random operands; attention kernel = {head['kernel_tflops'] / tf_r:.2f} of the latter")
     extra["dense_equiv_tops"] = head["dense_equiv_tops"]
     extra["sparsity"] = 1.0 - head["keep"]
     extra["plan_ms"] = head["plan_ms"]

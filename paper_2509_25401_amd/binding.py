@@ -52,6 +52,8 @@ def load_library():
     lib.sparse_gemm_q.restype = i32
     lib.sparse_gemm_q_stream.argtypes = [vp] * 5 + [i32] * 6 + [vp]
     lib.sparse_gemm_q_stream.restype = i32
+    lib.sparse_attn_probe_mfma.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.sparse_attn_probe_mfma.restype = i32
     lib.sparse_attn_plan_create.argtypes = [vp, vp] + [i32] * 6 + [vp, ctypes.POINTER(vp)]
     lib.sparse_attn_plan_create.restype = i32
     lib.sparse_attn_plan_run.argtypes = [vp] * 6 + [i32, vp]
@@ -164,6 +166,15 @@ def sparse_gemm_q(X, W, bias, cache_flags, Q, block_q, stream=None):
     if rc != 0:
         _raise(rc)
     return Q
+
+
+def sparse_attn_probe_mfma(random_operands: bool, launches: int = 6):
+    """(TFLOP/s, shader MHz) of an MFMA-only loop on the current device (measurement helper)."""
+    tf, mhz = ctypes.c_double(0), ctypes.c_double(0)
+    rc = load_library().sparse_attn_probe_mfma(1 if random_operands else 0, int(launches), ctypes.byref(tf), ctypes.byref(mhz))
+    if rc != 0:
+        _raise(rc)
+    return tf.value, mhz.value
 
 
 class SparseAttnPlan:

@@ -29,7 +29,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = pkg.load_library()
     names = _declared_functions()
-    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and "sparse_gemm_o" in names and "sparse_symbols_update" in names and "sparse_op_reuse" in names and "sparse_taylor_coefficients" in names and len(names) >= 17
+    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and "sparse_gemm_o" in names and "sparse_symbols_update" in names and "sparse_op_reuse" in names and "sparse_taylor_coefficients" in names and "sparse_attn_probe_mfma" in names and len(names) >= 18
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
     assert pkg.sparse_attn_version() >= 100
@@ -236,3 +236,11 @@ def test_plan_create_validation_precedes_any_device_work():
     assert lib.sparse_attn_plan_create(None, None, 1, 1, 256, 128, 128, 1, None, None) == -1
     assert lib.sparse_attn_plan_run(None, FAKE, FAKE, FAKE, None, FAKE, 128, None) == -1
     assert lib.sparse_attn_plan_destroy(None) == 0
+
+
+def test_probe_validation():
+    lib = pkg.load_library()
+    tf = ctypes.c_double(0)
+    assert lib.sparse_attn_probe_mfma(0, 0, ctypes.byref(tf), None) == -1
+    assert lib.sparse_attn_probe_mfma(0, 65, ctypes.byref(tf), None) == -1
+    assert lib.sparse_attn_probe_mfma(1, 3, None, None) == -1

@@ -92,3 +92,9 @@ def test_plan_without_symbols_is_dense_attention_and_skips_the_prepass_time():
     t_shot = timed(lambda: pkg.sparse_attn_fwd(case.Q, case.K, case.V, None, None, None, O1, 128, 128))
     print(f"[plan] 4608 tokens x 4 heads dense: stored plan {t_plan * 1e3:.1f} us/call, one-shot {t_shot * 1e3:.1f} us/call", flush=True)
     plan.destroy()
+
+
+def test_mfma_probe_reports_a_plausible_rate():
+    tf, mhz = pkg.sparse_attn_probe_mfma(True, launches=2)
+    print(f"[probe] MFMA-only loop, random operands: {tf:.0f} TFLOP/s at {mhz:.0f} MHz", flush=True)
+    assert 300.0 < tf < 2600.0 and 500.0 < mhz < 2600.0
