@@ -27,9 +27,7 @@ def gemm_o(O, W, bias, cache_flags, select, addend, block_q):
     C_out = W.shape[0]
     if W.shape != (C_out, H * D):
         raise ValueError("W must be [C_out, H*D]")
-    if L % block_q:
-        raise ValueError("L must be a multiple of block_q")
-    Tq = L // block_q
+    Tq = -(-L // block_q)      # Definition 1 counts ceil(L / b) blocks: the last token block may be short
     Of, Wf = _widen(O), _widen(W)
     out = np.zeros((B, L, C_out), dtype=np.float64)
     for b in range(B):

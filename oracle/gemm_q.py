@@ -58,9 +58,7 @@ def gemm_q(X, W, bias, cache_flags, block_q, H, D, Q_init_bits=None, norm_weight
     B, L, C = X.shape
     if W.shape != (H * D, C):
         raise ValueError("W must be [H*D, C]")
-    if L % block_q:
-        raise ValueError("L must be a multiple of block_q")
-    Tq = L // block_q
+    Tq = -(-L // block_q)      # Definition 1 counts ceil(L / b) blocks: the last token block may be short
     if cache_flags is not None and np.asarray(cache_flags).shape != (B, H, Tq):
         raise ValueError("cache_flags must be [B, H, Tq]")
     Q_bits = np.zeros((B, H, L, D), dtype=np.uint16) if Q_init_bits is None else np.array(Q_init_bits, dtype=np.uint16, copy=True)
@@ -87,6 +85,6 @@ def gemm_q(X, W, bias, cache_flags, block_q, H, D, Q_init_bits=None, norm_weight
 
 def computed_flops(cache_flags, B, H, L, C, D, block_q):
     """2*bq*D*C per computed (b,h,i) tile: the work the projection actually does."""
-    Tq = L // block_q
+    Tq = -(-L // block_q)
     n = B * H * Tq if cache_flags is None else int((np.asarray(cache_flags) == 0).sum())
     return 2.0 * block_q * D * C * n

@@ -93,3 +93,20 @@ def test_speedup_model_matches_segment_accounting_and_the_printed_example():
     for N in (4, 6, 8):
         work = (stage1 + stage2) + (N - 1) * stage2          # one Update step, N-1 Dispatch steps
         assert N * total / work == pytest.approx(oracle.gemm_o_speedup_model(N, 0.75))
+
+
+def test_short_last_token_block():
+    """ceil(L / b) token blocks: the heads of the short last block are selected by the last flag column."""
+    rng = np.random.default_rng(41)
+    B, H, L, D, C, bq = 1, 3, 40, 4, 6, 16
+    O = synth.normal_bf16(rng, (B, H, L, D))
+    W = synth.normal_bf16(rng, (C, H * D))
+    flags = np.array([[[0, 1, 1], [1, 0, 0], [0, 0, 1]]], dtype=np.uint8)
+    s1, _ = oracle.gemm_o(O, W, None, flags, 1, None, bq)
+    s0, _ = oracle.gemm_o(O, W, None, flags, 0, None, bq)
+    dense, _ = oracle.gemm_o(O, W, None, None, 0, None, 8)
+    assert s0.shape == (B, L, C) and np.abs(s0 + s1 - dense).max() < 1e-12
+    # tokens 32..39 belong to block 2: heads 0 and 2 are cached there, head 1 is computed
+    Of, Wf = bits_to_f64(O), bits_to_f64(W)
+    want = Of[0, 1, 32:] @ Wf[:, D:2 * D].T
+    assert np.abs(s0[0, 32:] - want).max() < 1e-12

@@ -141,3 +141,16 @@ def test_fused_projection_reduces_to_its_parts():
     zero = np.zeros_like(ang)
     n_only, _ = oracle.gemm_q(X, W, b, None, bq, H, D, eps=0.0, rope_cos=np.cos(zero), rope_sin=np.sin(zero))
     assert np.allclose((n_only ** 2).mean(axis=-1), 1.0, atol=1e-12)
+
+
+def test_short_last_token_block():
+    """Definition 1: ceil(L / b) blocks.  The flags are per block, the last block holds 40 - 32 = 8 tokens."""
+    B, L, C, H, D, bq = 1, 40, 12, 2, 4, 16
+    X, W, b, _ = _case(31, B, L, C, H, D, bq, cached=0.0)
+    flags = np.array([[[0, 1, 0], [1, 0, 1]]], dtype=np.uint8)
+    Q, bits = oracle.gemm_q(X, W, b, flags, bq, H, D)
+    full, _ = oracle.gemm_q(X, W, b, None, 8, H, D)            # block size that divides L: same projection everywhere
+    live = np.repeat(flags == 0, bq, axis=2)[:, :, :L]
+    assert Q.shape == (B, H, L, D)
+    assert np.abs(Q[live] - full[live]).max() == 0 and (Q[~live] == 0).all()
+    assert live[0, 0, 32:].all() and not live[0, 1, 32:].any()
