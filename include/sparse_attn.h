@@ -30,7 +30,7 @@
  *   - Supported shapes: D in {64, 128}; block_q, block_k in {64, 128}; any L >= 1 with
  *     Tq = ceil(L / block_q) <= 16384 and Tkv = ceil(L / block_k) (Definition 1): the last query
  *     block and the last key block may be short; nothing past row L - 1 of a head is read or
- *     written.  (The projections and the symbol generation below need L to be a multiple.)
+ *     written.  The projections below accept any L as well; the symbol generation needs a multiple.
  *   - "device" pointers are HIP device memory owned by the caller; the library never frees
  *     or keeps them.  "host" pointers are ordinary host memory.
  *   - Return value: 0 on success, a negative SPARSE_ATTN_ERR_* code otherwise; a message for
@@ -102,10 +102,11 @@ int sparse_attn_fwd_timed(const void* Q, const void* K, const void* V,
  *   W            device, bf16 [H*D, C]: one row per output feature (the layout a Linear layer
  *                stores), head h owns rows h*D .. (h+1)*D-1
  *   bias         device, bf16 [H*D], or NULL
- *   cache_flags  device, uint8 [B, H, L/block_q], same meaning as in sparse_attn_fwd, or NULL
+ *   cache_flags  device, uint8 [B, H, ceil(L/block_q)], same meaning as in sparse_attn_fwd, or NULL
  *   Q            device, bf16 [B, H, L, D], written for the computed blocks (fp32 accumulation,
  *                rounded to nearest even); must not overlap X or W
- * Supported: D and block_q in {64, 128}, C a multiple of 64, L a multiple of block_q.
+ * Supported: D and block_q in {64, 128}, C a multiple of 64; any L >= 1 (the last token block may be short,
+ * flags are [B, H, ceil(L / block_q)]).
  * Errors as for sparse_attn_fwd.  Allocates nothing.
  */
 int sparse_gemm_q(const void* X, const void* W, const void* bias, const uint8_t* cache_flags, void* Q,
@@ -177,11 +178,12 @@ int sparse_gemm_q_norm_rope(const void* X, const void* W, const void* bias, cons
  *   O            device, bf16 [B, H, L, D] (the attention output)
  *   W            device, bf16 [C_out, H*D]: one row per output feature (Linear layer layout)
  *   bias         device, bf16 [C_out], or NULL
- *   cache_flags  device, uint8 [B, H, L/block_q] or NULL
+ *   cache_flags  device, uint8 [B, H, ceil(L/block_q)] or NULL
  *   addend       device, bf16 [B, L, C_out], NULL, or Out itself (accumulate in place)
  *   Out          device, bf16 [B, L, C_out], written everywhere (fp32 accumulation, rounded to
  *                nearest even); must not overlap O or W
- * Supported: D and block_q in {64, 128}, H <= 64, C_out a multiple of 128, L a multiple of block_q.
+ * Supported: D and block_q in {64, 128}, H <= 64, C_out a multiple of 128; any L >= 1 (the last token block may
+ * be short, flags are [B, H, ceil(L / block_q)]).
  * Errors as for sparse_attn_fwd.  Allocates nothing.
  */
 int sparse_gemm_o(const void* O, const void* W, const void* bias, const uint8_t* cache_flags, int select_cached,

@@ -155,7 +155,7 @@ def sparse_attn_fwd_timed(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, bl
 
 def sparse_gemm_q(X, W, bias, cache_flags, Q, block_q, stream=None):
     """Sparse query projection on device tensors: X bf16 [B,L,C], W bf16 [H*D,C], bias bf16 [H*D] or None,
-    cache_flags uint8 [B,H,L/block_q] or None, Q bf16 [B,H,L,D] written in place for the computed blocks."""
+    cache_flags uint8 [B,H,ceil(L/block_q)] or None, Q bf16 [B,H,L,D] written in place for the computed blocks."""
     B, L, C = X.shape
     _, H, _, D = Q.shape
     if tuple(W.shape) != (H * D, C) or Q.shape[0] != B or Q.shape[2] != L:
@@ -240,7 +240,7 @@ def sparse_gemm_q_norm_rope(X, W, bias, norm_weight, eps, rope_cos, rope_sin, ca
 
 def sparse_gemm_o(O, W, bias, cache_flags, select_cached, addend, Out, block_q, stream=None):
     """Sparse output projection on device tensors: O bf16 [B,H,L,D], W bf16 [C_out,H*D], bias bf16 [C_out] or None,
-    cache_flags uint8 [B,H,L/block_q] or None, addend bf16 [B,L,C_out] / None / Out, Out bf16 [B,L,C_out] (written).
+    cache_flags uint8 [B,H,ceil(L/block_q)] or None, addend bf16 [B,L,C_out] / None / Out, Out bf16 [B,L,C_out] (written).
     select_cached = 1 sums the heads whose flag is set (stage 1, the cached bias), 0 the others (stage 2)."""
     B, H, L, D = O.shape
     C_out = W.shape[0]

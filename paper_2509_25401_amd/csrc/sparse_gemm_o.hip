@@ -94,6 +94,9 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
   const char* gW = p.W + (size_t)col * kBN * w_pitch;
   const char* gO = p.O + ((size_t)b * p.H * p.L + (size_t)i * BQ) * (size_t)(D * 2);   // head 0; head h adds h*L*D*2
 
+  // the last token block may be short: loads of missing rows re-read the last row that exists, their results
+  // are never stored
+  const int rows_valid = min(BQ, p.L - i * BQ);
   unsigned w_goff[W_LOAD], x_goff[X_LOAD];
 #pragma unroll
   for (int u = 0; u < W_LOAD; ++u) {
@@ -103,7 +106,7 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
 #pragma unroll
   for (int u = 0; u < X_LOAD; ++u) {
     const int r = (wave + u * NWAVES) * 8 + lane / 8;
-    x_goff[u] = (unsigned)(r * (D * 2) + (((lane % 8) ^ row_swizzle(r)) * 16));
+    x_goff[u] = (unsigned)(min(r, rows_valid - 1) * (D * 2) + (((lane % 8) ^ row_swizzle(r)) * 16));
   }
   int w_off[kStepK / 16], x_off[kStepK / 16];
 #pragma unroll
@@ -169,7 +172,8 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
   u32x4 add_bits[OUT_ITERS];
   if (p.addend) {
 #pragma unroll
-    for (int it = 0; it < OUT_ITERS; ++it) add_bits[it] = *(const u32x4*)(p.addend + out_offset(it));
+    for (int it = 0; it < OUT_ITERS; ++it)
+      if (it * (NT / 16) + tid / 16 < rows_valid) add_bits[it] = *(const u32x4*)(p.addend + out_offset(it));
   }
 
   // scalar walk over the selected heads, PARTS stages per head
@@ -253,7 +257,7 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
       pr[1] = (__bf16)v[2 * e + 1];
       pk[e] = __builtin_bit_cast(unsigned, pr);
     }
-    *(u32x4*)(p.Out + out_offset(it)) = pk;
+    if (token < rows_valid) *(u32x4*)(p.Out + out_offset(it)) = pk;
   }
 }
 
@@ -296,9 +300,9 @@ int sparse_gemm_o_stream(const void* O, const void* W, const void* bias, const u
   if (H > 64) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_o: at most 64 heads (got %d)", H);
   if (C_out % kBN)
     return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_o: C_out=%d must be a multiple of %d", C_out, kBN);
-  if (L % block_q) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: L=%d must be a multiple of block_q=%d", L, block_q);
   if ((long long)kBN * H * D * 2 >= (1LL << 31)) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_o: H*D too large");
-  const long long tiles = (long long)B * (L / block_q) * (C_out / kBN);
+  const int tq = (L + block_q - 1) / block_q;      // a short last block counts as a block
+  const long long tiles = (long long)B * tq * (C_out / kBN);
   if (tiles > 0x3fffffffLL) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_o: too many tiles (%lld)", tiles);
   if (!O || !W || !Out) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: O, W and Out must not be NULL");
   if (((uintptr_t)O | (uintptr_t)W | (uintptr_t)Out | (uintptr_t)addend) & 15)
@@ -318,7 +322,7 @@ int sparse_gemm_o_stream(const void* O, const void* W, const void* bias, const u
   p.Out = (char*)Out;
   p.H = H;
   p.L = L;
-  p.Tq = L / block_q;
+  p.Tq = tq;
   p.C_out = C_out;
   p.select = select_cached;
   hipStream_t stream = (hipStream_t)hip_stream;

@@ -80,6 +80,9 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
   const size_t row_pitch = (size_t)p.C * 2;
   const char* gW = p.W + (size_t)h * D * row_pitch;
   const char* gX = p.X + ((size_t)b * p.L + (size_t)i * BQ) * row_pitch;
+  // the last token block may be short: loads of missing rows re-read the last row that exists, their results
+  // are never stored
+  const int rows_valid = min(BQ, p.L - i * BQ);
 
   // per-lane global offsets of this wave's stage loads (8 rows of 128 bytes per instruction)
   unsigned w_goff[W_LOAD], x_goff[X_LOAD];
@@ -91,7 +94,7 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
 #pragma unroll
   for (int u = 0; u < X_LOAD; ++u) {
     const int r = (wave + u * NWAVES) * 8 + lane / 8;
-    x_goff[u] = (unsigned)(r * row_pitch + (((lane % 8) ^ row_swizzle(r)) * 16));
+    x_goff[u] = (unsigned)(min(r, rows_valid - 1) * row_pitch + (((lane % 8) ^ row_swizzle(r)) * 16));
   }
   // per-lane LDS offsets of the operand reads: row l32 of this wave's first 32-row block, k-step ks
   int w_off[kStepK / 16], x_off[kStepK / 16];
@@ -199,7 +202,9 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
       const float4* gc = (const float4*)(p.rope_cos + (size_t)i * BQ * (D / 2));
       const float4* gs = (const float4*)(p.rope_sin + (size_t)i * BQ * (D / 2));
       for (int e = tid; e < NV; e += NWAVES * 64) {
-        const float4 vc = gc[e], vs = gs[e];
+        const bool there = (4 * e) / (D / 2) < rows_valid;          // the tables have L rows
+        const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+        const float4 vc = there ? gc[e] : zero, vs = there ? gs[e] : zero;
         const int o = (4 * e) / (D / 2) * TS + (4 * e) % (D / 2);
         *(float2*)(tab + o) = make_float2(vc.x, vc.y);
         *(float2*)(tab + o + 2) = make_float2(vc.z, vc.w);
@@ -274,7 +279,7 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
         u32x2 pk;
         pk[0] = __builtin_bit_cast(unsigned, lo);
         pk[1] = __builtin_bit_cast(unsigned, hi);
-        *(u32x2*)(qrow0 + (size_t)c * 32 * (D * 2) + d0 * 2) = pk;
+        if (wm * 64 + 32 * c + l32 < rows_valid) *(u32x2*)(qrow0 + (size_t)c * 32 * (D * 2) + d0 * 2) = pk;
       }
     }
 }
@@ -312,9 +317,9 @@ int gemm_q_run(const void* X, const void* W, const void* bias, const uint8_t* ca
   if ((D != 64 && D != 128) || (block_q != 64 && block_q != 128))
     return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_q: D and block_q must be 64 or 128 (got %d, %d)", D, block_q);
   if (C % kStepK) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_q: C=%d must be a multiple of %d", C, kStepK);
-  if (L % block_q) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: L=%d must be a multiple of block_q=%d", L, block_q);
   if ((long long)128 * C * 2 >= (1LL << 31)) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_q: C=%d too large", C);
-  const long long tiles = (long long)B * H * (L / block_q);
+  const int tq = (L + block_q - 1) / block_q;      // a short last block counts as a block
+  const long long tiles = (long long)B * H * tq;
   if (tiles > 0x3fffffffLL) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_q: too many tiles (%lld)", tiles);
   if (!X || !W || !Q) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_q: X, W and Q must not be NULL");
   if (((uintptr_t)X | (uintptr_t)W | (uintptr_t)Q) & 15)
@@ -340,7 +345,7 @@ int gemm_q_run(const void* X, const void* W, const void* bias, const uint8_t* ca
   p.H = H;
   p.L = L;
   p.C = C;
-  p.Tq = L / block_q;
+  p.Tq = tq;
   p.norm_w = (const uint16_t*)norm_weight;
   p.rope_cos = rope_cos;
   p.rope_sin = rope_sin;

@@ -103,7 +103,6 @@ def _gemm_q(B=1, L=128, C=64, H=1, D=128, bq=128, X=FAKE, W=ctypes.c_void_p(0x20
 
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), -1), (dict(L=0), -1), (dict(C=0), -1), (dict(H=0), -1), (dict(D=0), -1), (dict(bq=0), -1),
-    (dict(L=192), -1),                   # not a multiple of block_q
     (dict(C=96), -2),                    # channels must come in stages of 64
     (dict(D=96), -2), (dict(bq=32), -2),
     (dict(X=None), -1), (dict(W=None), -1), (dict(Q=None), -1),
@@ -122,7 +121,7 @@ def _gemm_o(B=1, H=2, L=128, D=128, C_out=128, bq=128, sel=0, O=FAKE, W=ctypes.c
 
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), -1), (dict(H=0), -1), (dict(L=0), -1), (dict(D=0), -1), (dict(C_out=0), -1), (dict(bq=0), -1),
-    (dict(sel=2), -1), (dict(L=192), -1),
+    (dict(sel=2), -1),
     (dict(C_out=192), -2), (dict(D=96), -2), (dict(bq=32), -2), (dict(H=65), -2),
     (dict(O=None), -1), (dict(W=None), -1), (dict(Out=None), -1),
     (dict(Out=FAKE), -1),                                   # Out aliases O
@@ -217,7 +216,7 @@ def _gemm_q_nr(eps=1e-6, cos=ctypes.c_void_p(0x50000000), sin=ctypes.c_void_p(0x
     (dict(sin=None), -1), (dict(cos=None), -1),                 # only one of the two tables
     (dict(cos=ctypes.c_void_p(0x50000004)), -1),
     (dict(norm=ctypes.c_void_p(0x60000001)), -1),
-    (dict(L=192), -1), (dict(C=96), -2), (dict(D=96), -2),
+    (dict(L=0), -1), (dict(C=96), -2), (dict(D=96), -2),
 ])
 def test_gemm_q_norm_rope_argument_validation_precedes_any_device_work(kw, code):
     assert _gemm_q_nr(**kw) == code

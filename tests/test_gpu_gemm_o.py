@@ -95,3 +95,34 @@ def test_image_dit_shape_stage2_with_config3_flags():
     got = _run(O, W, bias, w.cache_flags, 0, Bc, bq)
     ref, ref_bits = oracle.gemm_o(O, W, bias, w.cache_flags, 0, Bc, bq)
     _check(got, ref, ref_bits, "gemm_o image-DiT stage2")
+
+
+@pytest.mark.parametrize("D,bq,L", [(128, 128, 1000), (64, 64, 200), (128, 64, 513), (64, 128, 90)])
+def test_short_last_token_block(D, bq, L):
+    """ceil(L / block_q) token blocks; nothing past token L - 1 may be read from O or the addend or written to Out."""
+    rng = np.random.default_rng(70 + L)
+    B, H, C = 1, 3, 256
+    Tq = -(-L // bq)
+    O = synth.normal_bf16(rng, (B, H, L, D))
+    W = synth.f32_to_bf16_bits((rng.standard_normal((C, H * D)) / np.sqrt(H * D)).astype(np.float32))
+    flags = (rng.random((B, H, Tq)) < 0.4).astype(np.uint8)
+    addend = synth.normal_bf16(rng, (B, L, C))
+    pad = 256
+    obuf = np.full((H * L + pad, D), 0x7FC0, dtype=np.uint16)        # NaN behind the last head
+    obuf[:H * L] = O.reshape(H * L, D)
+    dO = up_bf16(obuf)[:H * L].view(1, H, L, D)
+    abuf = np.full((L + pad, C), 0x7FC0, dtype=np.uint16)
+    abuf[:L] = addend[0]
+    dA = up_bf16(abuf)[:L].view(1, L, C)
+    outbuf = torch.from_numpy(np.full((L + pad, C), 0x4242, dtype=np.uint16).view(np.int16)).view(torch.bfloat16).to("cuda:0")
+    Out = outbuf[:L].view(1, L, C)
+    for select in (0, 1):
+        pkg.sparse_gemm_o(dO, up_bf16(W), None, up_u8(flags), select, dA, Out, bq)
+        torch.cuda.synchronize()
+        whole = down_bits(outbuf)
+        assert (whole[L:] == 0x4242).all(), "rows past the end of Out were written"
+        got = synth.bf16_bits_to_f32(whole[:L]).astype(np.float64)[None]
+        assert np.isfinite(got).all(), "something past the end of O or the addend was read"
+        ref, _ = oracle.gemm_o(O, W, None, flags, select, addend, bq)
+        err = np.abs(got - ref)
+        assert (err <= np.abs(ref) * 2.0 ** -8 + 2e-3).all(), f"select {select}: max violation {err.max()}"

@@ -153,3 +153,44 @@ def test_fused_norm_rope_full_width_sampled():
     got = _run_fused(X, W, b, g, 1e-6, cos, sin, flags, B, L, C, H, D, bq)
     ref, ref_bits = oracle.gemm_q(X, W, b, flags, bq, H, D, norm_weight=g, eps=float(np.float32(1e-6)), rope_cos=cos, rope_sin=sin)
     _check(got, ref, ref_bits, flags, bq, "gemm_q norm+rope C=3072")
+
+
+@pytest.mark.parametrize("D,bq,L", [(128, 128, 1000), (64, 64, 200), (128, 64, 513), (64, 128, 90)])
+def test_short_last_token_block(D, bq, L):
+    """ceil(L / block_q) token blocks; nothing past row L - 1 of X may be read, nothing past it of Q written."""
+    print(f"[case] gemm_q ragged D={D} bq={bq} L={L}", flush=True)
+    B, C, H = 1, 192, 3
+    X, W, b, _ = _case(60 + L, B, L, C, H, D, bq, cached=0.0)
+    Tq = -(-L // bq)
+    flags = (np.random.default_rng(61 + L).random((B, H, Tq)) < 0.3).astype(np.uint8)
+    flags[0, 0, -1] = 0                                   # the short block is computed for head 0 ...
+    flags[0, 1, -1] = 1                                   # ... and skipped for head 1
+    # X sits at the start of a larger buffer with NaN behind it, Q likewise with a marker behind it
+    pad = 256
+    xbuf = np.full((L + pad, C), 0x7FC0, dtype=np.uint16)
+    xbuf[:L] = X[0]
+    dX = up_bf16(xbuf)[:L].view(1, L, C)
+    qbuf = torch.from_numpy(np.full((H * L + pad, D), 0x4242, dtype=np.uint16).view(np.int16)).view(torch.bfloat16).to("cuda:0")
+    Q = qbuf[:H * L].view(1, H, L, D)
+    cos, sin = _rope_tables(L, D)
+    g = synth.f32_to_bf16_bits((1.0 + 0.2 * np.random.default_rng(62).standard_normal(D)).astype(np.float32))
+    for fused in (False, True):
+        qbuf.copy_(torch.from_numpy(np.full((H * L + pad, D), 0x4242, dtype=np.uint16).view(np.int16)).view(torch.bfloat16))
+        if fused:
+            pkg.sparse_gemm_q_norm_rope(dX, up_bf16(W), up_bf16(b), up_bf16(g), 1e-6, torch.from_numpy(cos).to("cuda:0"),
+                                        torch.from_numpy(sin).to("cuda:0"), up_u8(flags), Q, bq)
+            ref, ref_bits = oracle.gemm_q(X, W, b, flags, bq, H, D, norm_weight=g, eps=float(np.float32(1e-6)), rope_cos=cos, rope_sin=sin)
+        else:
+            pkg.sparse_gemm_q(dX, up_bf16(W), up_bf16(b), up_u8(flags), Q, bq)
+            ref, ref_bits = oracle.gemm_q(X, W, b, flags, bq, H, D)
+        torch.cuda.synchronize()
+        whole = down_bits(qbuf)
+        assert (whole[H * L:] == 0x4242).all(), "rows past the end of Q were written"
+        got = whole[:H * L].reshape(1, H, L, D)
+        skipped = np.repeat(flags != 0, bq, axis=2)[:, :, :L]
+        assert (got[skipped] == 0x4242).all()
+        vals = synth.bf16_bits_to_f32(got).astype(np.float64)[~skipped]
+        assert np.isfinite(vals).all(), "something past the end of X was read"
+        err = np.abs(vals - ref[~skipped])
+        assert (err <= np.abs(ref[~skipped]) * 2.0 ** -8 + 1e-3).all()
+        assert (got[~skipped] == ref_bits[~skipped]).mean() > 0.98
