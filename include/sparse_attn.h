@@ -30,7 +30,7 @@
  *   - Supported shapes: D in {64, 128}; block_q, block_k in {64, 128}; any L >= 1 with
  *     Tq = ceil(L / block_q) <= 16384 and Tkv = ceil(L / block_k) (Definition 1): the last query
  *     block and the last key block may be short; nothing past row L - 1 of a head is read or
- *     written.  The projections below accept any L as well; the symbol generation needs a multiple.
+ *     written.  The projections and the symbol generation below accept any L as well.
  *   - "device" pointers are HIP device memory owned by the caller; the library never frees
  *     or keeps them.  "host" pointers are ordinary host memory.
  *   - Return value: 0 on success, a negative SPARSE_ATTN_ERR_* code otherwise; a message for
@@ -228,7 +228,8 @@ void sparse_taylor_coefficients(int order, float steps, float* coef);
  * Sparse-symbol generation of an Update step (Section 3.3 "Logical Masks Generation", Equation 1; the
  * tau_kv and S_q rules of the settings table in the appendix).  From the step's Q and K it writes the
  * two symbol arrays that sparse_attn_fwd, sparse_gemm_q and sparse_gemm_o read at the following steps.
- * Per (batch, head), with T = L / block blocks of which the first text_tokens / block are text:
+ * Per (batch, head), with T = ceil(L / block) blocks (a short last block is pooled over the tokens that exist)
+ * of which the first text_tokens / block are text:
  *   1. q~, k~ = per-block means of the query / key rows; P~ = row softmax of q~ k~^T / sqrt(D)
  *   2. C_v = sum over text rows of P~[row, vision block v]; G_v = sum over text columns j of
  *      softmax over v of P~[vision block v, j]

@@ -56,9 +56,9 @@ def compressed_map(Q, K, block):
     """Steps 1-2.  Q, K: uint16 bf16 bits [B,H,L,D].  Returns P~ as fp64 [B,H,T,T]."""
     Qf, Kf = _widen(Q), _widen(K)
     B, H, L, D = Qf.shape
-    T = L // block
-    qt = Qf.reshape(B, H, T, block, D).mean(axis=3)
-    kt = Kf.reshape(B, H, T, block, D).mean(axis=3)
+    T = -(-L // block)          # a short last block counts as a block; its mean is over the tokens that exist
+    qt = np.stack([Qf[:, :, t * block:(t + 1) * block].mean(axis=2) for t in range(T)], axis=2)
+    kt = np.stack([Kf[:, :, t * block:(t + 1) * block].mean(axis=2) for t in range(T)], axis=2)
     S = np.einsum("bhid,bhjd->bhij", qt, kt) / np.sqrt(D)
     return _softmax(S, axis=-1)
 
@@ -87,9 +87,9 @@ def update_symbols(Q, K, block, text_tokens, tau_c, tau_kv, s_q=0.0, tie_rel=1e-
       own_value    fp64  [B,H,T,T]    P~ itself (how far a near-tie can move a cumulative sum)
     """
     B, H, L, D = np.asarray(Q).shape
-    if L % block or text_tokens % block or not (0 < text_tokens < L):
-        raise ValueError("L and the text length must be multiples of the block size, with vision tokens left over")
-    T, n_t = L // block, text_tokens // block
+    if text_tokens % block or not (0 < text_tokens < L):
+        raise ValueError("the text length must be a multiple of the block size, with vision tokens left over")
+    T, n_t = -(-L // block), text_tokens // block
     P = compressed_map(Q, K, block)
     flags = np.zeros((B, H, T), dtype=np.uint8)
     flag_margin = np.full((B, H, T), np.inf)

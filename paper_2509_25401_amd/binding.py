@@ -309,9 +309,9 @@ def sparse_symbols_update(Q, K, cache_flags, kv_mask, block, text_tokens, tau_c,
     B, H, L, D = Q.shape
     if tuple(K.shape) != (B, H, L, D):
         raise ValueError("Q and K must have the same shape [B,H,L,D]")
-    T = L // block
+    T = -(-L // block)
     if tuple(cache_flags.shape) != (B, H, T) or tuple(kv_mask.shape) != (B, H, T, (T + 7) // 8):
-        raise ValueError("cache_flags must be [B,H,T] and kv_mask [B,H,T,ceil(T/8)] with T = L/block")
+        raise ValueError("cache_flags must be [B,H,T] and kv_mask [B,H,T,ceil(T/8)] with T = ceil(L/block)")
     rc = load_library().sparse_symbols_update_stream(_dev_ptr(Q, "Q"), _dev_ptr(K, "K"),
                                                      _dev_ptr(cache_flags, "cache_flags"), _dev_ptr(kv_mask, "kv_mask"),
                                                      int(B), int(H), int(L), int(D), int(block), int(text_tokens),

@@ -86,14 +86,18 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // pooled[which][block][d] = mean over the block's rows; grid (n_blocks, 2), which = 0 for Q, 1 for K
 template <int D>
 __global__ void __launch_bounds__(256) pool_blocks(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
-                                                   float* __restrict__ pooled, int block, long long n_blocks) {
+                                                   float* __restrict__ pooled, int block, int T, int L,
+                                                   long long n_blocks) {
   constexpr int TPR = D / 8;          // threads per row, 8 bf16 = 16 bytes each
   constexpr int RPP = 256 / TPR;      // rows per pass
   __shared__ float part[RPP][D];
-  const uint16_t* src = (blockIdx.y ? K : Q) + (size_t)blockIdx.x * block * D;
+  // block t of head bh; the last block of a head may be short: the mean is over the rows that exist
+  const int bh = blockIdx.x / T, t = blockIdx.x - bh * T;
+  const int rows = min(block, L - t * block);
+  const uint16_t* src = (blockIdx.y ? K : Q) + ((size_t)bh * L + (size_t)t * block) * D;
   const int c = threadIdx.x % TPR, r0 = threadIdx.x / TPR;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int r = r0; r < block; r += RPP) {
+  for (int r = r0; r < rows; r += RPP) {
     const uint4 v = *(const uint4*)(src + (size_t)r * D + c * 8);
     const unsigned w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -108,7 +112,7 @@ __global__ void __launch_bounds__(256) pool_blocks(const uint16_t* __restrict__ 
   if (threadIdx.x < D) {
     float s = 0.f;
     for (int r = 0; r < RPP; ++r) s += part[r][threadIdx.x];
-    pooled[((size_t)blockIdx.y * n_blocks + blockIdx.x) * D + threadIdx.x] = s * (1.0f / (float)block);
+    pooled[((size_t)blockIdx.y * n_blocks + blockIdx.x) * D + threadIdx.x] = s / (float)rows;
   }
 }
 
@@ -360,13 +364,12 @@ int sparse_symbols_update_stream(const void* Q, const void* K, uint8_t* cache_fl
                    block);
   if ((D != 64 && D != 128) || (block != 64 && block != 128))
     return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: D and block must be 64 or 128 (got %d, %d)", D, block);
-  if (L % block || text_tokens % block)
-    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: L=%d and text_tokens=%d must be multiples of block=%d", L,
-                   text_tokens, block);
+  if (text_tokens % block)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: text_tokens=%d must be a multiple of block=%d", text_tokens, block);
   if (text_tokens <= 0 || text_tokens >= L)
     return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: text_tokens=%d must leave text and vision blocks (L=%d)",
                    text_tokens, L);
-  const int T = L / block, n_t = text_tokens / block;
+  const int T = (L + block - 1) / block, n_t = text_tokens / block;   // a short last block counts as a block
   if (T > kMaxBlocks) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: %d blocks exceed %d", T, kMaxBlocks);
   if (T - n_t > 256 * 32) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: too many vision blocks (%d)", T - n_t);
   if (!(tau_c >= 0.f && tau_c <= 1.f) || !(tau_kv >= 0.f && tau_kv <= 1.f) || !(s_q >= 0.f && s_q <= 1.f))
@@ -401,13 +404,13 @@ int sparse_symbols_update_stream(const void* Q, const void* K, uint8_t* cache_fl
   }
   if (D == 128) {
     hipLaunchKernelGGL(pool_blocks<128>, dim3((unsigned)n_blocks, 2), dim3(256), 0, stream, (const uint16_t*)Q,
-                       (const uint16_t*)K, pooled, block, n_blocks);
+                       (const uint16_t*)K, pooled, block, T, L, n_blocks);
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(map_rows<128>, dim3((unsigned)(B * H * groups)), dim3(256), map_lds, stream, pooled, n_blocks, T, T_pad, n_t,
                        row_bytes, scale, tau_kv, kv_mask, text_rows, text_cols);
   } else {
     hipLaunchKernelGGL(pool_blocks<64>, dim3((unsigned)n_blocks, 2), dim3(256), 0, stream, (const uint16_t*)Q,
-                       (const uint16_t*)K, pooled, block, n_blocks);
+                       (const uint16_t*)K, pooled, block, T, L, n_blocks);
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(map_rows<64>, dim3((unsigned)(B * H * groups)), dim3(256), map_lds, stream, pooled, n_blocks, T, T_pad, n_t,
                        row_bytes, scale, tau_kv, kv_mask, text_rows, text_cols);

@@ -140,7 +140,7 @@ def _symbols(B=1, H=1, L=512, D=128, blk=128, text=128, tau_c=0.5, tau_kv=0.1, s
 
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), -1), (dict(H=0), -1), (dict(L=0), -1), (dict(D=0), -1), (dict(blk=0), -1),
-    (dict(L=576), -1), (dict(text=64), -1),                 # not multiples of the block
+    (dict(text=64), -1),                                    # text length not a multiple of the block
     (dict(text=0), -1), (dict(text=512), -1),               # no text blocks / no vision blocks
     (dict(D=96), -2), (dict(blk=32), -2),
     (dict(L=128 * 2049, text=128), -2),                      # more blocks than the kernels are sized for

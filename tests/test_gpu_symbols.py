@@ -136,3 +136,25 @@ def test_video_size_symbols_and_the_attention_they_drive():
             err = np.abs(synth.bf16_bits_to_f32(got[b, h, rows]).astype(np.float64) - ref_o[n])
             assert err.max() <= 1e-2 and err.mean() <= 1e-3
     print(f"[symbols] video33k pipeline: {len(items)} sampled blocks ({n_cached} cached) match the oracle", flush=True)
+
+
+@pytest.mark.parametrize("L,D,block,text", [(1000, 128, 128, 128), (4200, 64, 64, 128), (2561, 128, 128, 256)])
+def test_short_last_block(L, D, block, text):
+    B, H = 1, 2
+    T = -(-L // block)
+    Q, K = synth.structured_qk(synth.BASE_SEED + 500 + L, B, H, T * block, D, block)
+    Q, K = np.ascontiguousarray(Q[:, :, :L]), np.ascontiguousarray(K[:, :, :L])
+    tau_c, tau_kv = f32(0.5), f32(0.2)
+    ref = oracle.update_symbols(Q, K, block, text, tau_c, tau_kv)
+    flags, mask = run_gpu_ragged(Q, K, block, text, tau_c, tau_kv)
+    compare(ref, flags, mask, T, f"ragged L{L}_D{D}_b{block}", max_ambiguous=0.05)
+
+
+def run_gpu_ragged(Q, K, block, text, tau_c, tau_kv):
+    B, H, L, D = Q.shape
+    T = -(-L // block)
+    flags = torch.full((B, H, T), 0xAA, dtype=torch.uint8, device=dev())
+    mask = torch.full((B, H, T, (T + 7) // 8), 0xAA, dtype=torch.uint8, device=dev())
+    pkg.sparse_symbols_update(up_bf16(Q), up_bf16(K), flags, mask, block, text, tau_c, tau_kv)
+    torch.cuda.synchronize()
+    return flags.cpu().numpy(), mask.cpu().numpy()

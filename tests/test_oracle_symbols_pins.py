@@ -112,3 +112,19 @@ def test_degrade_rule_and_block_permutation():
     robust = ~base["flag_tie"][0, 0] & (base["flag_margin"][0, 0] > 1e-9)
     assert (p["cache_flags"][0, 0][robust[perm]] == base["cache_flags"][0, 0][perm][robust[perm]]).all()
     assert (p["M_s"][0, 0] == base["M_s"][0, 0][perm][:, perm]).mean() > 0.999
+
+
+def test_short_last_block_is_pooled_over_the_tokens_that_exist():
+    B, H, L, D, blk, text = 1, 1, 14, 4, 4, 4           # 4 blocks, the last one holds 2 tokens
+    Q, K = synth.structured_qk(6, B, H, 16, D, blk)
+    Q, K = np.ascontiguousarray(Q[:, :, :L]), np.ascontiguousarray(K[:, :, :L])
+    P = oracle.compressed_map(Q, K, blk)
+    assert P.shape == (1, 1, 4, 4)
+    Qf, Kf = bits_to_f64(Q)[0, 0], bits_to_f64(K)[0, 0]
+    qt = [Qf[0:4].mean(0), Qf[4:8].mean(0), Qf[8:12].mean(0), (Qf[12] + Qf[13]) / 2]
+    kt = [Kf[0:4].mean(0), Kf[4:8].mean(0), Kf[8:12].mean(0), (Kf[12] + Kf[13]) / 2]
+    S = np.array([[qi @ kj / 2.0 for kj in kt] for qi in qt])          # sqrt(D) = 2
+    E = np.exp(S - S.max(axis=1, keepdims=True))
+    assert np.abs(P[0, 0] - E / E.sum(axis=1, keepdims=True)).max() < 1e-14
+    out = oracle.update_symbols(Q, K, blk, text, 0.5, 0.2)
+    assert out["cache_flags"].shape == (1, 1, 4) and out["M_s"].shape == (1, 1, 4, 4)
