@@ -81,3 +81,42 @@ def test_attention_with_forecast_composes_the_two_branches():
     # order 0 falls back to the plain copy of Algorithm 1
     O0, bits0 = oracle.attention_with_forecast(w.Q, w.K, w.V, w.cache_flags, mask, [w.O_cache], [1.0], 64, 64)
     assert (bits0 == ref_bits).all()
+
+
+def test_finite_difference_refresh_on_polynomial_trajectories():
+    """Features sampled every N steps.  Linear motion: one refresh pair gives the exact slope and the forecast is
+    exact.  f(t) = t^2: backward differences give slope 3N and curvature 2 after the samples at 0, N, 2N, so the
+    second-order forecast k steps on is 4N^2 + 3Nk + k^2 (the true value is (2N + k)^2: the slope lags by N)."""
+    N, k = 4.0, 3.0
+    a = np.array([[1.0, -2.0, 0.5]])
+    b = np.array([[0.25, 3.0, -1.0]])
+    terms = [np.zeros((1, 3), dtype=np.uint16) for _ in range(3)]
+    n_valid = 0
+    for t in (0.0, N, 2 * N):
+        terms = oracle.taylor_update(exact_bf16(a + b * t), terms, n_valid, N)
+        n_valid = min(n_valid + 1, 3)
+    assert (bits_to_f64(terms[1]) == b).all() and (bits_to_f64(terms[2]) == 0).all()
+    f, _ = oracle.op_reuse(terms, oracle.taylor_coefficients(2, k))
+    assert (f == a + b * (2 * N + k)).all()
+    # quadratic
+    terms = [np.zeros((1, 1), dtype=np.uint16) for _ in range(3)]
+    n_valid = 0
+    for t in (0.0, N, 2 * N):
+        terms = oracle.taylor_update(exact_bf16(np.array([[t * t]])), terms, n_valid, N)
+        n_valid = min(n_valid + 1, 3)
+    assert bits_to_f64(terms[0])[0, 0] == 4 * N * N and bits_to_f64(terms[1])[0, 0] == 3 * N and bits_to_f64(terms[2])[0, 0] == 2.0
+    f, _ = oracle.op_reuse(terms, oracle.taylor_coefficients(2, k))
+    assert f[0, 0] == 4 * N * N + 3 * N * k + k * k
+
+
+def test_refresh_uses_only_as_many_orders_as_there_were_refreshes():
+    rng = np.random.default_rng(9)
+    x0, x1 = synth.normal_bf16(rng, (5, 8)), synth.normal_bf16(rng, (5, 8))
+    junk = [synth.normal_bf16(rng, (5, 8)) for _ in range(3)]
+    first = oracle.taylor_update(x0, junk, 0, 5.0)
+    assert (first[0] == x0).all() and (first[1] == 0).all() and (first[2] == 0).all()
+    second = oracle.taylor_update(x1, first, 1, 5.0)
+    assert (second[0] == x1).all() and (second[2] == 0).all()
+    want = (bits_to_f64(x1) - bits_to_f64(x0)) / 5.0
+    back = bits_to_f64(second[1])
+    assert np.abs(back - want).max() <= np.abs(want).max() * 2.0 ** -8
