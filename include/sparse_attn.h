@@ -225,6 +225,22 @@ int sparse_op_reuse(const void* const* terms, const float* coef, int n_terms, vo
 void sparse_taylor_coefficients(int order, float steps, float* coef);
 
 /*
+ * Refresh of the stored terms at an Update step.  The paper only says that cached features are forecast from
+ * "stored features and their derivatives"; the derivatives are estimated the way the forecasting method it cites
+ * does, by backward finite differences over the Update interval:
+ *     new[0] = fresh,   new[d] = (new[d-1] - old[d-1]) / interval  for 1 <= d <= n_valid,   new[d] = 0 beyond
+ * with n_valid the number of terms that were valid before this call (0 at the first refresh; the caller then
+ * raises it by one per refresh up to n_terms).  Differences are taken in fp32 between the stored bf16 values and
+ * rounded once per term.
+ *   fresh   device, bf16, n_elems values (the freshly computed feature, e.g. the attention output O or B_c)
+ *   terms   HOST array of n_terms (1..4) DEVICE pointers, each n_elems bf16 values, updated in place; they must
+ *           not overlap each other or fresh; all 16-byte aligned; n_elems a positive multiple of 8
+ * Errors as for sparse_attn_fwd.  Allocates nothing.
+ */
+int sparse_taylor_update(const void* fresh, void* const* terms, int n_terms, int n_valid, float interval,
+                         unsigned long long n_elems, void* hip_stream);
+
+/*
  * Sparse-symbol generation of an Update step (Section 3.3 "Logical Masks Generation", Equation 1; the
  * tau_kv and S_q rules of the settings table in the appendix).  From the step's Q and K it writes the
  * two symbol arrays that sparse_attn_fwd, sparse_gemm_q and sparse_gemm_o read at the following steps.

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     sparse_attn_fwd_forecast,
     sparse_op_reuse,
     sparse_taylor_coefficients,
+    sparse_taylor_update,
     sparse_attn_profile_begin,
     sparse_attn_profile_end,
     sparse_attn_pack_mask,

@@ -71,6 +71,8 @@ def load_library():
     lib.sparse_attn_fwd_forecast.restype = i32
     lib.sparse_op_reuse.argtypes = [vp, vp, i32, vp, ctypes.c_ulonglong, vp]
     lib.sparse_op_reuse.restype = i32
+    lib.sparse_taylor_update.argtypes = [vp, vp, i32, i32, f32, ctypes.c_ulonglong, vp]
+    lib.sparse_taylor_update.restype = i32
     lib.sparse_taylor_coefficients.argtypes = [i32, f32, vp]
     lib.sparse_taylor_coefficients.restype = None
     lib.sparse_symbols_update.argtypes = [vp] * 4 + [i32] * 6 + [f32] * 3
@@ -294,6 +296,21 @@ def sparse_op_reuse(terms, coef, out, stream=None):
     if rc != 0:
         _raise(rc)
     return out
+
+
+def sparse_taylor_update(fresh, terms, n_valid, interval, stream=None):
+    """Refresh the stored forecast terms in place from a freshly computed feature (backward finite differences over
+    `interval` steps); n_valid = number of terms that were valid before this call."""
+    n = fresh.numel()
+    for t in terms:
+        if t.numel() != n:
+            raise ValueError("every term must have as many elements as fresh")
+    ptrs = (ctypes.c_void_p * len(terms))(*[_dev_ptr(t, f"terms[{d}]").value for d, t in enumerate(terms)])
+    rc = load_library().sparse_taylor_update(_dev_ptr(fresh, "fresh"), ptrs, len(terms), int(n_valid), float(interval),
+                                             int(n), _stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
+    return terms
 
 
 def sparse_taylor_coefficients(order, steps):

@@ -29,7 +29,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = pkg.load_library()
     names = _declared_functions()
-    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and "sparse_gemm_o" in names and "sparse_symbols_update" in names and "sparse_op_reuse" in names and "sparse_taylor_coefficients" in names and "sparse_attn_probe_mfma" in names and len(names) >= 18
+    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and "sparse_gemm_o" in names and "sparse_symbols_update" in names and "sparse_op_reuse" in names and "sparse_taylor_coefficients" in names and "sparse_attn_probe_mfma" in names and "sparse_taylor_update" in names and len(names) >= 19
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
     assert pkg.sparse_attn_version() >= 100
@@ -243,3 +243,21 @@ def test_probe_validation():
     assert lib.sparse_attn_probe_mfma(0, 0, ctypes.byref(tf), None) == -1
     assert lib.sparse_attn_probe_mfma(0, 65, ctypes.byref(tf), None) == -1
     assert lib.sparse_attn_probe_mfma(1, 3, None, None) == -1
+
+
+def _taylor_update(n_terms=2, n_valid=1, interval=5.0, fresh=FAKE, terms=(0x20000000, 0x30000000), n=1024, null_terms=False):
+    t = None if null_terms else _ptr_array(list(terms))
+    return pkg.load_library().sparse_taylor_update(fresh, t, n_terms, n_valid, interval, n, None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n_terms=0), -2), (dict(n_terms=5), -2), (dict(n_valid=-1), -1), (dict(n_valid=3), -1),
+    (dict(interval=0.0), -1), (dict(interval=float("nan")), -1), (dict(interval=float("inf")), -1),
+    (dict(fresh=None), -1), (dict(null_terms=True), -1), (dict(n=0), -1), (dict(n=1001), -1),
+    (dict(terms=(0x20000000, None)), -1), (dict(terms=(0x20000004, 0x30000000)), -1),
+    (dict(terms=(0x20000000, 0x20000100)), -1),            # two terms overlap
+    (dict(terms=(0x10000 + 64, 0x30000000)), -1),          # a term overlaps fresh
+])
+def test_taylor_update_argument_validation_precedes_any_device_work(kw, code):
+    assert _taylor_update(**kw) == code
+    assert pkg.sparse_attn_last_error() != ""

@@ -103,3 +103,34 @@ def test_forecast_feeds_the_output_projection():
     err = np.abs(synth.bf16_bits_to_f32(down_bits(Out)).astype(np.float64) - ref)
     print(f"[op_reuse] forecast bias + GEMM-O: max-abs {err.max():.3e}", flush=True)
     assert err.max() <= 6e-2 and err.mean() <= 1e-2             # bf16 rounding of values of size ~4
+
+
+@pytest.mark.parametrize("n_terms", [1, 2, 3, 4])
+def test_refresh_of_the_terms_matches_oracle_over_several_updates(n_terms):
+    """Four Update steps in a row, then a forecast: the stored terms follow the oracle's finite differences."""
+    rng = np.random.default_rng(synth.BASE_SEED + 90 + n_terms)
+    shape = (2, 1000, 24)
+    interval = 5.0
+    host_terms = [np.zeros(shape, dtype=np.uint16) for _ in range(n_terms)]
+    dev_terms = [torch.full(shape, 7.0, dtype=torch.bfloat16, device=dev()) for _ in range(n_terms)]   # junk to be replaced
+    n_valid = 0
+    for step in range(4):
+        fresh = synth.normal_bf16(rng, shape)
+        host_terms = oracle.taylor_update(fresh, host_terms, n_valid, interval)
+        pkg.sparse_taylor_update(up_bf16(fresh), dev_terms, n_valid, interval)
+        torch.cuda.synchronize()
+        n_valid = min(n_valid + 1, n_terms)
+        for d in range(n_terms):
+            got = down_bits(dev_terms[d])
+            same = (got == host_terms[d]).mean()
+            assert same > 0.999, f"update {step}, term {d}: only {same * 100:.3f} % bit-identical"
+            diff = np.abs(synth.bf16_bits_to_f32(got).astype(np.float64) - synth.bf16_bits_to_f32(host_terms[d]).astype(np.float64))
+            ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(synth.bf16_bits_to_f32(host_terms[d]).astype(np.float64)), 1e-30))) - 7)
+            assert (diff <= ulp).all()
+            host_terms[d] = got        # continue from what the device stored, so that one-ulp ties do not accumulate
+    out = torch.zeros(shape, dtype=torch.bfloat16, device=dev())
+    coef = pkg.sparse_taylor_coefficients(n_terms - 1, 2.0)
+    pkg.sparse_op_reuse(dev_terms, coef, out)
+    torch.cuda.synchronize()
+    ref, _ = oracle.op_reuse(host_terms, coef)
+    check_forecast(down_bits(out), ref, host_terms, coef, f"forecast after 4 refreshes, n_terms={n_terms}")
