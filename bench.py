@@ -156,8 +156,26 @@ def main():
         torch.cuda.synchronize()
         extra["config4"]["ms_per_step_taylor_order1"] = (time.perf_counter() - t) / few * 1e3
         log(f"config4 with first-order forecast in the cache branch: {extra['config4']['ms_per_step_taylor_order1']:.3f} ms/step")
-        del Oc, fl4, mk4
+        del fl4, mk4
         Q.copy_(up_bf16(w.Q)); K.copy_(up_bf16(w.K)); V.copy_(up_bf16(w.V))
+        # the three operating points the paper's kernel figure quotes (A100: 4.6x, 4.97x, ~9.4x): 80 % block-sparse
+        # skipping, 80 % feature caching, 90 % combined (half of the vision q-blocks cached, the rest at 20 % keep)
+        pts = {}
+        rngp = np.random.default_rng(np.random.SeedSequence([synth.BASE_SEED + 6]))
+        def vision_flags(frac):
+            f = np.zeros((w.B, w.H, w.Tq), dtype=np.uint8)
+            n = int(round(frac * (w.Tq - 2)))
+            for hh in range(w.H):
+                f[0, hh, 2 + rngp.permutation(w.Tq - 2)[:n]] = 1
+            return f
+        M20 = synth.video_sweep_mask(rngp, w.B, w.H, w.Tq, 2, 0.2, False)
+        for name, M, f in (("bss80", M20, None), ("fc80", None, vision_flags(0.8)), ("combined90", M20, vision_flags(0.5))):
+            r = run_case(M, f, Oc if f is not None else None, few, warm, f"paper point {name}")
+            sp = dense["ms_per_step"] / r["ms_per_step"]
+            pts[name] = dict(sparsity=1.0 - r["keep"], ms_per_step=r["ms_per_step"], eff_tflops=r["eff_tflops"],
+                             speedup_vs_dense=sp, ideal_speedup=1.0 / r["keep"], speedup_over_ideal=sp * r["keep"])
+        extra["paper_operating_points"] = pts
+        del Oc
     if not args.no_extras:
         # 2K-image shape (17K tokens: 128 x 128 patches + 512 text tokens), dense and at 25 % keep, through a stored plan
         L17, T17 = 16896, 132
