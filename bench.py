@@ -44,7 +44,7 @@ def main():
     ap.add_argument("--keep", type=float, default=0.25, help="keep ratio of the headline mask")
     ap.add_argument("--no-extras", action="store_true", help="skip the dense run, the sweep and config 4")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--cpu-blocks", type=int, default=256, help="query blocks in the oracle's timed sample")
+    ap.add_argument("--cpu-blocks", type=int, default=1280, help="query blocks in the oracle's timed sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--heads", type=int, default=24, help="heads (24 = the named workload; fewer only for quick checks)")
