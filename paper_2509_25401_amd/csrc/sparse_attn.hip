@@ -17,9 +17,12 @@
 //               the row sum none until the end, and the exponentiated S^T accumulators are the
 //               B operand of the O^T product without any data movement.  The reference of the
 //               exponent is the C operand of the first S^T MFMA; it is checked after the fact
-//               (the sum of a sub-tile's weights shows whether a score left the allowed range)
-//               and moves only then, so the steady state takes no row maximum at all.  A copy
-//               item moves one cached block O_cache -> O.
+//               (the sum of a block's weights shows whether a score left the allowed range)
+//               and moves only then, so the steady state takes no row maximum at all.  The
+//               vector instructions of the softmax sit between matrix instructions that do not
+//               depend on them (weights of one 32-key block under the scores of the next and
+//               under the O^T product of the previous), where they issue in the shadow of the
+//               wave's own MFMAs.  A copy item moves one cached block O_cache -> O.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdarg.h>
@@ -420,80 +423,60 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(t1, t2, 0, 1, 2, 3, 4, 5, 6, 7));
       };
 
-      // S^T[key][query] - reference, for 64 keys: two 32x32 blocks
+      // The sub-tile's 64 keys are two blocks of 32 (one 32x32 S^T accumulator each).  Within this wave the
+      // instruction stream is ordered so that the vector work of the softmax sits BETWEEN matrix instructions
+      // that do not depend on it -- a wave's VALU instructions issue while its own earlier MFMA is still in the
+      // matrix pipe, but only if they come right behind it in program order:
+      //   S0:  scores of block 0                      (KS MFMAs)
+      //   S1:  scores of block 1      || weights of block 0   (KS MFMAs, 32 vector instructions spread over them)
+      //   PV0: O^T += V^T P^T, block 0 || weights of block 1
+      //   PV1: O^T += V^T P^T, block 1
+      // Weights are rounded to bf16 for the O^T product and the row sum adds up the same rounded values.
+      // k-slot s of lane-half h of the O^T MFMA maps to key 32*kb2 + 16*ksp + 8*(s/4) + 4*h + s%4, which is
+      // exactly the key order of the S^T accumulator registers 8*ksp .. 8*ksp+7.
+      // The exponent's reference is checked after the fact, block by block: the weights are formed against
+      // the current reference straight away, and only if their sum shows that one of them left the allowed
+      // range is the block's row maximum taken, the reference moved and the block's weights formed again.
+      constexpr int CPS = 8 / KS;     // weight chunks (two scores each) per MFMA slot of a group
       f32x16 s[2];
-      bf16x8 ka[NQK];
-#pragma unroll
-      for (int t = 0; t < kPre; ++t) ka[t] = k_read(t);
-      __builtin_amdgcn_s_setprio(kMfmaPrio);
-#pragma unroll
-      for (int t = 0; t < NQK; ++t) {
-        if (t + kPre < NQK) ka[t + kPre] = k_read(t + kPre);
-        s[t / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t], qf[t % KS], t % KS == 0 ? neg_ref : s[t / KS], 0, 0, 0);
-      }
-      __builtin_amdgcn_s_setprio(0);
-      if constexpr (RAGGED) {
-        if (valid < kKeys) {
-          // accumulator register e of block kb2 is key 32*kb2 + 8*(e/4) + 4*half + e%4 of the sub-tile
-          const int lim = valid - 4 * half;
-#pragma unroll
-          for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) s[kb2][e] = (32 * kb2 + 8 * (e / 4) + e % 4 >= lim) ? -INFINITY : s[kb2][e];
-        }
-      }
-      // first operands of the O^T product: fetched now, consumed after the softmax
-      bf16x8 va[NPV];
-#pragma unroll
-      for (int t = 0; t < kPre; ++t) va[t] = v_read(t);
-
-      // Weights, rounded to bf16 for the O^T product; the row sum adds up the same rounded values.
-      // k-slot s of lane-half h of the O^T MFMA maps to key 32*kb2 + 16*ksp + 8*(s/4) + 4*h + s%4,
-      // which is exactly the key order of the S^T accumulator registers 8*ksp .. 8*ksp+7.
-      // The exponent's reference is checked after the fact: the weights are formed against the current
-      // reference straight away, and only if their sum shows that one of them left the allowed range
-      // (or on the first sub-tile, which has no reference yet) is the row maximum taken, the reference
-      // moved, and the weights formed again.  In the common case the softmax costs no maximum at all.
       bf16x8 pb[4];
       bf16x2 ones;
       ones[0] = (__bf16)1.0f;
       ones[1] = (__bf16)1.0f;
-      float dl = 0.f;
-      auto weights = [&]() {
-        dl = 0.f;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) pb[g][e] = (__bf16)__builtin_amdgcn_exp2f(s[g >> 1][8 * (g & 1) + e]);
-#pragma unroll
-          for (int e = 0; e < 8; e += 2) {
-            bf16x2 pr;
-            pr[0] = pb[g][e];
-            pr[1] = pb[g][e + 1];
-            dl = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, dl, false);
-          }
-        }
+      auto chunk = [&](int kb2, int c, float& dl) {
+        const int g = 2 * kb2 + c / 4, e = 2 * (c % 4);
+        bf16x2 pr;
+        pr[0] = (__bf16)__builtin_amdgcn_exp2f(s[kb2][8 * (g & 1) + e]);
+        pr[1] = (__bf16)__builtin_amdgcn_exp2f(s[kb2][8 * (g & 1) + e + 1]);
+        pb[g][e] = pr[0];
+        pb[g][e + 1] = pr[1];
+        dl = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, dl, false);
       };
-      if (!first) weights();
-      // !(dl <= limit) also catches an overflowed (infinite or NaN) sum
-      if (first || __builtin_amdgcn_ballot_w64(!(dl <= kSumLimit)) != 0) {
-        // this lane sees 32 of the 64 scores of its query row; the other half sits in lane ^ 32
-        float mx = s[0][0];
+      auto mask_block = [&](int kb2) {
+        // accumulator register e of block kb2 is key 32*kb2 + 8*(e/4) + 4*half + e%4 of the sub-tile
+        const int lim = valid - 4 * half;
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
+        for (int e = 0; e < 16; ++e) s[kb2][e] = (32 * kb2 + 8 * (e / 4) + e % 4 >= lim) ? -INFINITY : s[kb2][e];
+      };
+      // Moves the reference to the row maximum of block kb2 (upwards only, except on the very first block of an
+      // item, which sets it).  `other_too`: block 1's scores were formed against the old reference as well.
+      auto move_reference = [&](int kb2, bool other_too) {
+        float mx = s[kb2][0];
 #pragma unroll
-          for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb2][e]);
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[kb2][e]);
         {
+          // this lane sees 16 of the 32 scores of its query row in this block; the other half sits in lane ^ 32
           const unsigned bits = __builtin_bit_cast(unsigned, mx);
           const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
           mx = fmaxf(__builtin_bit_cast(float, (unsigned)sw[0]), __builtin_bit_cast(float, (unsigned)sw[1]));
         }
-        // move the reference: to the row maximum on the first sub-tile, upwards only afterwards
         const float d = first ? mx : fmaxf(mx, 0.f);
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
+        for (int e = 0; e < 16; ++e) s[kb2][e] -= d;
+        if (other_too) {
 #pragma unroll
-          for (int e = 0; e < 16; ++e) s[kb2][e] -= d;
+          for (int e = 0; e < 16; ++e) s[1][e] -= d;
+        }
         if (!first) {
           const float alpha = __builtin_amdgcn_exp2f(-d);
           l_run *= alpha;
@@ -506,12 +489,69 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) neg_ref[e] = nr;
         first = false;
-        weights();
-      }
-      l_run += dl;
-      __builtin_amdgcn_s_setprio(kMfmaPrio);
+      };
+
+      bf16x8 ka[NQK];
 #pragma unroll
-      for (int t = 0; t < NPV; ++t) {
+      for (int t = 0; t < kPre; ++t) ka[t] = k_read(t);
+      __builtin_amdgcn_s_setprio(kMfmaPrio);
+      // ---- S0
+#pragma unroll
+      for (int t = 0; t < KS; ++t) {
+        if (t + kPre < NQK) ka[t + kPre] = k_read(t + kPre);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t], qf[t], t == 0 ? neg_ref : s[0], 0, 0, 0);
+      }
+      if constexpr (RAGGED) {
+        if (valid < kKeys) mask_block(0);
+      }
+      if (first) move_reference(0, false);     // the first block of an item sets the reference; block 1 is not formed yet
+      // ---- S1 || weights of block 0
+      float dl0 = 0.f;
+#pragma unroll
+      for (int t = 0; t < KS; ++t) {
+        if (KS + t + kPre < NQK) ka[KS + t + kPre] = k_read(KS + t + kPre);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[KS + t], qf[t], t == 0 ? neg_ref : s[1], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int cc = 0; cc < CPS; ++cc) chunk(0, t * CPS + cc, dl0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (RAGGED) {
+        if (valid < kKeys) mask_block(1);
+      }
+      // first operands of the O^T product
+      bf16x8 va[NPV];
+#pragma unroll
+      for (int t = 0; t < kPre; ++t) va[t] = v_read(t);
+      // !(sum <= limit) also catches an overflowed (infinite or NaN) sum
+      if (__builtin_amdgcn_ballot_w64(!(dl0 <= kSumLimit)) != 0) {
+        move_reference(0, true);
+        dl0 = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) chunk(0, c, dl0);
+      }
+      l_run += dl0;
+      // ---- PV0 || weights of block 1
+      float dl1 = 0.f;
+#pragma unroll
+      for (int t = 0; t < NPV / 2; ++t) {
+        if (t + kPre < NPV) va[t + kPre] = v_read(t + kPre);
+        o[t % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[t], pb[t / DB], o[t % DB], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int cc = 0; cc < CPS; ++cc) chunk(1, t * CPS + cc, dl1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (__builtin_amdgcn_ballot_w64(!(dl1 <= kSumLimit)) != 0) {
+        move_reference(1, false);
+        dl1 = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) chunk(1, c, dl1);
+      }
+      l_run += dl1;
+      // ---- PV1
+#pragma unroll
+      for (int t = NPV / 2; t < NPV; ++t) {
         if (t + kPre < NPV) va[t + kPre] = v_read(t + kPre);
         o[t % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[t], pb[t / DB], o[t % DB], 0, 0, 0);
       }
