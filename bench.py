@@ -29,7 +29,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 # HBM bytes per launch of the attention kernel on the headline workload, from the rocprofv3 --pmc
 # passes summarised in profiles/attn_kernel_video33k_keep25_counters.txt (FETCH_SIZE and WRITE_SIZE,
 # each scaled by the same counter's reading for a plain 1 GiB copy).  Only valid for that workload.
-MEASURED_TRAFFIC_BYTES = {"keep=0.25 heads=24": 8388539 * 2048 + 198802 * 1024}
+MEASURED_TRAFFIC_BYTES = {"keep=0.25 heads=24": 8252733 * 2048 + 198598 * 1024}
 
 
 def log(msg):
