@@ -2,7 +2,7 @@
 Equation 1, and the tau_q / tau_kv / S_q descriptions of the settings table in the appendix).
 
 TEST INFRASTRUCTURE ONLY.  The steps follow the paper's order; every place where its text leaves a choice
-is listed in DESIGN.md ("readings") and repeated next to the step.  Per (batch, head), with block size b
+is stated next to the step.  Per (batch, head), with block size b
 (= b_q = b_k, granularity n = 1), T = L / b blocks, the first n_t = N_text / b blocks being text:
 
  1. token gathering: q~_i, k~_j = mean of the b query / key rows of block i / j;
