@@ -214,7 +214,7 @@ def test_config3_image_cache_and_skip():
     check_against_oracle(w, got, ref, ref_bits, "config3")
 
 
-@pytest.mark.parametrize("profile", ["growing", "shrinking", "huge", "spiky"])
+@pytest.mark.parametrize("profile", ["growing", "shrinking", "huge", "spiky", "staircase"])
 def test_score_ranges_that_force_the_exponent_reference_to_move(profile):
     """The kernel exponentiates against a lazily updated reference.  Keys whose scale changes along the sequence
     make later scores exceed (growing, spiky), fall far below (shrinking) or overflow (huge) what the reference was
@@ -232,6 +232,10 @@ def test_score_ranges_that_force_the_exponent_reference_to_move(profile):
         scale = 0.1 + 2.9 * pos / L                      # scores grow 30x along the keys
     elif profile == "shrinking":
         scale = 3.0 - 2.9 * pos / L
+    elif profile == "staircase":
+        # every 32-key block is 8x louder than the one before it over the first 128 keys: the reference set by the
+        # first block of an item has to move at the second block of the same sub-tile and at both blocks of the next
+        scale = np.where(pos < 128, 0.05 * 8.0 ** np.minimum(pos // 32, 3), 0.05).astype(np.float32)
     elif profile == "huge":
         scale = np.full_like(pos, 40.0)                  # |score * log2(e)| reaches the hundreds: exp2 overflows
     else:
