@@ -321,6 +321,92 @@ def main():
             f"kept pairs {keep_frac:.2f}")
         del Qs, Ks, fl, mk
     if not args.no_extras:
+        # one caching interval of the attention module (Section 3.2 with the projections of Section 3.5): an Update
+        # step (everything dense, plus symbol generation, the plan of the interval, the cached bias of GEMM-O stage 1
+        # and the refresh of its forecast terms) and N - 1 Dispatch steps (GEMM-Q skips cached tiles, attention runs
+        # the stored plan and leaves cached blocks alone because GEMM-O takes them from OP_reuse(B_c), GEMM-O skips
+        # cached heads), against N dense steps.  Symbols: the 90 % combined point (half of the vision query blocks
+        # cached, the rest at 20 % keep); the symbol generation is timed on the data but its output is not used.
+        N_int, order, C = 6, 1, 3072
+        g = torch.Generator(device=dev); g.manual_seed(11)
+        Xp = torch.randn((w.B, w.L, C), device=dev, generator=g).to(torch.bfloat16)
+        Wq = (torch.randn((w.H * w.D, C), device=dev, generator=g) / C ** 0.5).to(torch.bfloat16)
+        Wo = (torch.randn((C, w.H * w.D), device=dev, generator=g) / (w.H * w.D) ** 0.5).to(torch.bfloat16)
+        gain = torch.ones(w.D, device=dev, dtype=torch.bfloat16)
+        ang = torch.arange(w.L, device=dev, dtype=torch.float32)[:, None] * (10000.0 ** (-torch.arange(w.D // 2, device=dev, dtype=torch.float32) / (w.D // 2)))[None, :]
+        rc, rs = torch.cos(ang).contiguous(), torch.sin(ang).contiguous()
+        Q2 = torch.empty_like(Q)
+        Bc = torch.empty((w.B, w.L, C), device=dev, dtype=torch.bfloat16)
+        add, Yo = torch.empty_like(Bc), torch.empty_like(Bc)
+        termsB = [torch.zeros_like(Bc) for _ in range(order + 1)]
+        rngi = np.random.default_rng(np.random.SeedSequence([synth.BASE_SEED + 8]))
+        Mi = synth.video_sweep_mask(rngi, w.B, w.H, w.Tq, 2, 0.2, False)
+        fi = np.zeros((w.B, w.H, w.Tq), dtype=np.uint8)
+        for hh in range(w.H):
+            fi[0, hh, 2 + rngi.permutation(w.Tq - 2)[:(w.Tq - 2) // 2]] = 1
+        dfl, dmk = up_u8(fi), up_u8(pkg.sparse_attn_pack_mask(Mi))
+        sfl = torch.empty((w.B, w.H, w.Tq), dtype=torch.uint8, device=dev)
+        smk = torch.empty((w.B, w.H, w.Tq, (w.Tkv + 7) // 8), dtype=torch.uint8, device=dev)
+        kept_i, total_i = pkg.sparse_attn_count_kept(fi, pkg.sparse_attn_pack_mask(Mi), w.B, w.H, w.L, w.block_q, w.block_k)
+
+        def dense_step():
+            pkg.sparse_gemm_q_norm_rope(Xp, Wq, None, gain, 1e-6, rc, rs, None, Q2, w.block_q)
+            pkg.sparse_attn_fwd(Q2, K, V, None, None, None, O, w.block_q, w.block_k)
+            pkg.sparse_gemm_o(O, Wo, None, None, 0, None, Yo, w.block_q)
+
+        def update_step(n_valid):
+            pkg.sparse_gemm_q_norm_rope(Xp, Wq, None, gain, 1e-6, rc, rs, None, Q2, w.block_q)
+            pkg.sparse_symbols_update(Q2, K, sfl, smk, w.block_q, 2 * w.block_q, 0.5, 0.75)
+            plan = pkg.SparseAttnPlan(dfl, dmk, w.B, w.H, w.L, w.block_q, w.block_k)
+            pkg.sparse_attn_fwd(Q2, K, V, None, None, None, O, w.block_q, w.block_k)
+            pkg.sparse_gemm_o(O, Wo, None, dfl, 1, None, Bc, w.block_q)
+            pkg.sparse_taylor_update(Bc, termsB, n_valid, N_int)
+            pkg.sparse_gemm_o(O, Wo, None, dfl, 0, Bc, Yo, w.block_q)
+            return plan
+
+        def dispatch_step(plan, k):
+            pkg.sparse_gemm_q_norm_rope(Xp, Wq, None, gain, 1e-6, rc, rs, dfl, Q2, w.block_q)
+            plan.run(Q2, K, V, None, O)
+            pkg.sparse_op_reuse(termsB, pkg.sparse_taylor_coefficients(order, float(k)), add)
+            pkg.sparse_gemm_o(O, Wo, None, dfl, 0, add, Yo, w.block_q)
+
+        def timed(fn, reps):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / reps * 1e3
+
+        n_valid = [0]
+
+        def interval():
+            plan = update_step(n_valid[0])
+            n_valid[0] = min(n_valid[0] + 1, order + 1)
+            for k in range(1, N_int):
+                dispatch_step(plan, k)
+            torch.cuda.synchronize()
+            plan.destroy()
+
+        for _ in range(2):
+            dense_step()
+        interval(); interval()
+        dense_ms = timed(dense_step, 6)
+        interval_ms = timed(interval, 3)
+        plan = update_step(2)
+        disp_ms = timed(lambda: dispatch_step(plan, 1), 6)
+        torch.cuda.synchronize()
+        plan.destroy()
+        extra["attention_module_interval"] = dict(
+            N=N_int, forecast_order=order, sparsity=1.0 - kept_i / total_i, cached_frac=float(fi.mean()),
+            dense_step_ms=dense_ms, dispatch_step_ms=disp_ms, interval_ms=interval_ms,
+            update_step_ms=interval_ms - (N_int - 1) * disp_ms,
+            speedup_dispatch_vs_dense=dense_ms / disp_ms, speedup_interval_vs_dense=N_int * dense_ms / interval_ms)
+        log(f"attention module over an interval of {N_int} steps at {extra['attention_module_interval']['sparsity']:.2f} sparsity: "
+            f"dense step {dense_ms:.3f} ms, dispatch step {disp_ms:.3f} ms ({dense_ms / disp_ms:.2f}x), interval {interval_ms:.3f} ms "
+            f"({N_int * dense_ms / interval_ms:.2f}x over {N_int} dense steps)")
+        del Xp, Wq, Wo, Q2, Bc, add, Yo, termsB, rc, rs, ang
+    if not args.no_extras:
         # what this device sustains on MFMAs alone (its clock under matrix load depends on the operand data)
         tf_c, mhz_c = pkg.sparse_attn_probe_mfma(False)
         tf_r, mhz_r = pkg.sparse_attn_probe_mfma(True)
