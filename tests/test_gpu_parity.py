@@ -197,6 +197,30 @@ def test_non_default_stream():
     assert (down_bits(O) == base).all()
 
 
+def test_two_streams_in_flight_do_not_share_scratch():
+    """The pre-pass buffers (decoded symbols, work list, queue counters) belong to the stream of the call: two calls
+    of different shapes that are in flight on two streams at once give what each gives alone."""
+    _note("two streams in flight")
+    wa = synth.random_case(61, 1, 6, 2048, 128, 128, 128, keep=0.4, cached_frac=0.2)
+    wb = synth.random_case(62, 2, 3, 1024, 64, 64, 64, keep=0.6, cached_frac=0.3)
+    ca, cb = DeviceCase(wa), DeviceCase(wb)
+    base_a, base_b = ca.run(), cb.run()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    outs_a = [torch.zeros_like(ca.Q) for _ in range(3)]
+    outs_b = [torch.zeros_like(cb.Q) for _ in range(3)]
+    torch.cuda.synchronize()
+    for Oa, Ob in zip(outs_a, outs_b):
+        with torch.cuda.stream(sa):
+            pkg.sparse_attn_fwd(ca.Q, ca.K, ca.V, ca.flags, ca.mask, ca.Oc, Oa, 128, 128)
+        with torch.cuda.stream(sb):
+            pkg.sparse_attn_fwd(cb.Q, cb.K, cb.V, cb.flags, cb.mask, cb.Oc, Ob, 64, 64)
+    sa.synchronize()
+    sb.synchronize()
+    for Oa, Ob in zip(outs_a, outs_b):
+        assert (down_bits(Oa) == base_a).all()
+        assert (down_bits(Ob) == base_b).all()
+
+
 # ------------------------------------------------------------------ the paper-shaped configurations
 def test_config2_image_skip_only():
     _note("config 2 image-DiT skip only")
