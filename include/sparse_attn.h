@@ -145,6 +145,14 @@ int sparse_attn_plan_create(const uint8_t* cache_flags, const uint8_t* kv_mask, 
 int sparse_attn_plan_run(const sparse_attn_plan* plan, const void* Q, const void* K, const void* V, const void* O_cache,
                          void* O, int D, void* hip_stream);
 int sparse_attn_plan_destroy(sparse_attn_plan* plan);
+/*
+ * sparse_attn_plan_run with the Taylor-series OP_reuse of sparse_attn_fwd_forecast in its cache branch (Section
+ * 3.2's Dispatch step with forecast features: stored symbols, stored pre-pass, cached blocks forecast from their
+ * terms).  O_terms, coef, n_terms as for sparse_attn_fwd_forecast; everything else as for sparse_attn_plan_run.
+ */
+int sparse_attn_plan_run_forecast(const sparse_attn_plan* plan, const void* Q, const void* K, const void* V,
+                                  const void* const* O_terms, const float* coef, int n_terms, void* O, int D,
+                                  void* hip_stream);
 
 /*
  * GEMM-Q with the two token-wise operations of Equation 2 fused into its epilogue:

@@ -58,6 +58,8 @@ def load_library():
     lib.sparse_attn_plan_create.restype = i32
     lib.sparse_attn_plan_run.argtypes = [vp] * 6 + [i32, vp]
     lib.sparse_attn_plan_run.restype = i32
+    lib.sparse_attn_plan_run_forecast.argtypes = [vp] * 6 + [i32, vp, i32, vp]
+    lib.sparse_attn_plan_run_forecast.restype = i32
     lib.sparse_attn_plan_destroy.argtypes = [vp]
     lib.sparse_attn_plan_destroy.restype = i32
     lib.sparse_gemm_q_norm_rope.argtypes = [vp] * 4 + [ctypes.c_float] + [vp] * 4 + [i32] * 6 + [vp]
@@ -199,6 +201,22 @@ class SparseAttnPlan:
         rc = load_library().sparse_attn_plan_run(self._h, _dev_ptr(Q, "Q"), _dev_ptr(K, "K"), _dev_ptr(V, "V"),
                                                  _dev_ptr(O_cache, "O_cache", True), _dev_ptr(O, "O"), int(D),
                                                  _stream_ptr(stream))
+        if rc != 0:
+            _raise(rc)
+        return O
+
+    def run_forecast(self, Q, K, V, O_terms, coef, O, stream=None):
+        """run() with OP_reuse = sum_d coef[d] * O_terms[d] in the cache branch (see sparse_attn_fwd_forecast)."""
+        B, H, L, D = Q.shape
+        if (B, H, L) != self.shape:
+            raise ValueError("Q does not have the shape the plan was made for")
+        for t in O_terms:
+            if tuple(t.shape) != (B, H, L, D):
+                raise ValueError("every term must have the shape of Q")
+        ptrs, cf = _term_arrays(O_terms, coef, "O_terms")
+        rc = load_library().sparse_attn_plan_run_forecast(self._h, _dev_ptr(Q, "Q"), _dev_ptr(K, "K"), _dev_ptr(V, "V"),
+                                                          ptrs, cf, len(O_terms), _dev_ptr(O, "O"), int(D),
+                                                          _stream_ptr(stream))
         if rc != 0:
             _raise(rc)
         return O

@@ -983,6 +983,16 @@ int sparse_attn_plan_run(const sparse_attn_plan* plan, const void* Q, const void
              nullptr, false, nullptr, plan);
 }
 
+int sparse_attn_plan_run_forecast(const sparse_attn_plan* plan, const void* Q, const void* K, const void* V,
+                                  const void* const* O_terms, const float* coef, int n_terms, void* O, int D,
+                                  void* hip_stream) {
+  if (!plan) return fail(SPARSE_ATTN_ERR_INVALID, "plan must not be NULL");
+  const Shape& s = plan->s;
+  const Forecast fc = {O_terms, coef, n_terms};
+  return run(Q, K, V, nullptr, nullptr, nullptr, O, s.B, s.H, s.L, D, s.bq, s.bk, (hipStream_t)hip_stream, nullptr,
+             nullptr, false, &fc, plan);
+}
+
 int sparse_attn_plan_destroy(sparse_attn_plan* plan) {
   if (!plan) return 0;
   const hipError_t e = hipFree(plan->mem);     // waits for work that still uses the buffer

@@ -234,6 +234,7 @@ def test_plan_create_validation_precedes_any_device_work():
         h = ctypes.c_void_p(0x1234)
     assert lib.sparse_attn_plan_create(None, None, 1, 1, 256, 128, 128, 1, None, None) == -1
     assert lib.sparse_attn_plan_run(None, FAKE, FAKE, FAKE, None, FAKE, 128, None) == -1
+    assert lib.sparse_attn_plan_run_forecast(None, FAKE, FAKE, FAKE, None, None, 1, FAKE, 128, None) == -1
     assert lib.sparse_attn_plan_destroy(None) == 0
 
 

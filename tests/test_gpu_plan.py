@@ -36,6 +36,31 @@ def test_plan_reproduces_the_one_shot_call_bit_for_bit(D, bq, bk):
     plan.destroy()
 
 
+@pytest.mark.parametrize("D,bq,bk,n_terms", [(128, 128, 128, 2), (64, 64, 64, 3)])
+def test_plan_with_forecast_reproduces_the_one_shot_forecast(D, bq, bk, n_terms):
+    """Stored plan + Taylor forecast in the cache branch: the same bits as sparse_attn_fwd_forecast (whose parity
+    with the oracle is checked where that entry point is tested), run after run."""
+    w = synth.random_case(synth.BASE_SEED + 95 + n_terms, 1, 4, 1152, D, bq, bk, keep=0.5, cached_frac=0.4)
+    rng = np.random.default_rng(synth.BASE_SEED + 96 + n_terms)
+    terms = [up_bf16(w.O_cache)] + [up_bf16(synth.normal_bf16(rng, w.Q.shape)) for _ in range(n_terms - 1)]
+    coef = pkg.sparse_taylor_coefficients(n_terms - 1, 3.0)
+    case = DeviceCase(w)
+    want = fresh_O(w)
+    pkg.sparse_attn_fwd_forecast(case.Q, case.K, case.V, case.flags, case.mask, terms, coef, want, bq, bk)
+    plan = pkg.SparseAttnPlan(case.flags, case.mask, w.B, w.H, w.L, bq, bk)
+    torch.cuda.synchronize()
+    rows = np.repeat(w.cache_flags != 0, bq, axis=2)
+    assert rows.any() and (~rows).any()
+    for rep in range(2):
+        O = fresh_O(w)
+        plan.run_forecast(case.Q, case.K, case.V, terms, coef, O)
+        torch.cuda.synchronize()
+        assert (down_bits(O) == down_bits(want)).all(), f"run {rep} differs from the one-shot forecast"
+    # and it is not the plain copy: the forecast moved the cached blocks away from term 0
+    assert (down_bits(want)[rows] != w.O_cache[rows]).any()
+    plan.destroy()
+
+
 @pytest.mark.parametrize("n,L", [(2, 1024), (3, 896), (4, 2048)])
 def test_granularity_decodes_like_the_expanded_symbols(n, L):
     B, H, D, blk = 1, 2, 128, 128
