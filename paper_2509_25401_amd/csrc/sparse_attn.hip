@@ -244,9 +244,14 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
   const float c = p.scale_log2;
 
   // Per-lane offsets, the same for every item.
-  unsigned k_goff[NLOAD], v_goff[NLOAD];   // global byte offsets inside a sub-tile (swizzle applied to the source)
+  // Global byte offsets inside a sub-tile (swizzle applied to the source).  The swizzles repeat every 16 rows, so
+  // the offsets of load t and load t + TP differ by a constant that goes into the (scalar) base address.
+  constexpr int TP = NWAVES * ROWS_PER_INST >= 16 ? 1 : 16 / (NWAVES * ROWS_PER_INST);
+  constexpr int TSTEP = TP * NWAVES * ROWS_PER_INST * ROWB;
+  static_assert(NLOAD % TP == 0, "loads of a wave must be whole swizzle periods");
+  unsigned k_goff[TP], v_goff[TP];
 #pragma unroll
-  for (int t = 0; t < NLOAD; ++t) {
+  for (int t = 0; t < TP; ++t) {
     const int r = (wave + t * NWAVES) * ROWS_PER_INST + lane / CH;
     const int pch = lane % CH;
     k_goff[t] = (unsigned)(r * ROWB + ((pch ^ k_swizzle<D>(r)) * 16));
@@ -379,7 +384,8 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       return 32 * w_idx + b;
     };
 
-    auto issue_loads = [&](int j, int sub, auto buf_c) {
+    // loads lo .. hi-1 of this wave's NLOAD for sub-tile (j, sub)
+    auto issue_loads = [&](int j, int sub, auto buf_c, int lo, int hi) {
       constexpr int buf = decltype(buf_c)::value;
       const size_t tile_off = ((size_t)j * BK + (size_t)sub * kKeys) * ROWB;
       const char* gK = Kh + tile_off;
@@ -388,7 +394,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
         const int valid = p.L - (j * BK + sub * kKeys);     // >= 1: sub-tiles past the end are never requested
         if (valid < kKeys) {
 #pragma unroll
-          for (int t = 0; t < NLOAD; ++t) {
+          for (int t = lo; t < hi; ++t) {
             const int r = (wave + t * NWAVES) * ROWS_PER_INST + lane / CH;
             const int pch = lane % CH;
             const int src_row = min(r, valid - 1);            // LDS row r receives the last row that exists
@@ -400,14 +406,16 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
         }
       }
 #pragma unroll
-      for (int t = 0; t < NLOAD; ++t) {
+      for (int t = lo; t < hi; ++t) {
         const unsigned dst = (unsigned)(buf * TILEB + (wave + t * NWAVES) * 1024);
-        sa_load_to_lds_16B(gK, k_goff[t], lds_base + dst);
-        sa_load_to_lds_16B(gV, v_goff[t], lds_base + 2 * TILEB + dst);
+        sa_load_to_lds_16B(gK + (t / TP) * TSTEP, k_goff[t % TP], lds_base + dst);
+        sa_load_to_lds_16B(gV + (t / TP) * TSTEP, v_goff[t % TP], lds_base + 2 * TILEB + dst);
       }
     };
 
-    auto compute = [&](auto buf_c, int valid) {   // valid: keys of this sub-tile that exist (RAGGED only)
+    // valid: keys of this sub-tile that exist (RAGGED only); (nj, nsub): the sub-tile to fetch into the other
+    // buffer meanwhile, nj < 0 if there is none
+    auto compute = [&](auto buf_c, auto other_c, int valid, int nj, int nsub) {
       // the buffer index is a compile-time constant, so every LDS address below is a per-lane
       // register that never changes plus an immediate offset
       constexpr int buf = decltype(buf_c)::value;
@@ -500,11 +508,18 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       for (int t = 0; t < KS; ++t) {
         if (t + kPre < NQK) ka[t + kPre] = k_read(t + kPre);
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t], qf[t], t == 0 ? neg_ref : s[0], 0, 0, 0);
+        // the next sub-tile's loads go out here, a few behind each matrix instruction, instead of in one
+        // burst in front of the first one
+        if (nj >= 0) issue_loads(nj, nsub, other_c, t * NLOAD / KS, (t + 1) * NLOAD / KS);
       }
       if constexpr (RAGGED) {
         if (valid < kKeys) mask_block(0);
       }
       if (first) move_reference(0, false);     // the first block of an item sets the reference; block 1 is not formed yet
+      // first operands of the O^T product: on their way while the scores of block 1 are formed
+      bf16x8 va[NPV];
+#pragma unroll
+      for (int t = 0; t < kPre; ++t) va[t] = v_read(t);
       // ---- S1 || weights of block 0
       float dl0 = 0.f;
 #pragma unroll
@@ -519,10 +534,6 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       if constexpr (RAGGED) {
         if (valid < kKeys) mask_block(1);
       }
-      // first operands of the O^T product
-      bf16x8 va[NPV];
-#pragma unroll
-      for (int t = 0; t < kPre; ++t) va[t] = v_read(t);
       // !(sum <= limit) also catches an overflowed (infinite or NaN) sum
       if (__builtin_amdgcn_ballot_w64(!(dl0 <= kSumLimit)) != 0) {
         move_reference(0, true);
@@ -564,7 +575,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     using Buf1 = std::integral_constant<int, 1>;
     int j = next_block();
     int sub = 0;
-    if (j >= 0) issue_loads(j, 0, Buf0{});
+    if (j >= 0) issue_loads(j, 0, Buf0{}, 0, NLOAD);
     auto step = [&](auto cur, auto other) {
       int nj = j, nsub = sub + 1;
       if constexpr (RAGGED) {
@@ -576,8 +587,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       }
       sa_wait_vmem();
       __syncthreads();   // this sub-tile has landed for every wave; the other buffer is free
-      if (nj >= 0) issue_loads(nj, nsub, other);
-      compute(cur, RAGGED ? p.L - (j * BK + sub * kKeys) : kKeys);
+      compute(cur, other, RAGGED ? p.L - (j * BK + sub * kKeys) : kKeys, nj, nsub);
       j = nj;
       sub = nsub;
     };
