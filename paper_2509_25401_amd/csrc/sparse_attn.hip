@@ -58,6 +58,12 @@ constexpr int kXcds = 8;               // accelerator dies (XCDs) of the MI355X,
 constexpr int kMaxHeadGroups = 64;    // head groups per (XCD, bucket) in the ordering histogram
 constexpr int kMaxTq = 16384;
 constexpr unsigned kCopyFlag = 0x80000000u;
+// Queue counters: every queue head sits in a 128-byte line of its own (all workgroups of an XCD bump the same
+// head once per item; eight heads in one line would make every workgroup of the chip contend for that line),
+// the queue ends, which the attention kernel only reads, in a line that is never written while it runs.
+constexpr int kHeadStride = 32;                   // words between two queue heads
+constexpr int kEndOffset = 8 * kHeadStride;       // first queue end
+constexpr int kQueueWords = kEndOffset + 64;      // 1280 bytes
 constexpr int kHwRegXccId = (3 << 11) | 20;   // s_getreg operand: 4 bits at offset 0 of hardware register 20 (XCC_ID)
 constexpr int kOrderThreads = 1024;
 constexpr int kMaxTerms = 4;            // stored feature + up to three derivatives
@@ -72,7 +78,7 @@ struct AttnParams {
   char* O;
   const uint32_t* words;   // [N][nw32] decoded symbol words
   const uint32_t* order;   // [N] work list: row | kCopyFlag
-  uint32_t* queues;        // kXcds queue heads, then kXcds queue ends
+  uint32_t* queues;        // kXcds queue heads at [q * kHeadStride], kXcds queue ends at [kEndOffset + q]
   int N;                   // B*H*Tq
   int Tq;
   int Tkv;
@@ -129,7 +135,11 @@ __global__ void __launch_bounds__(256) plan_rows(const uint8_t* __restrict__ cac
 
 // Copies the initial queue heads and ends of a stored plan into the live ones its next run consumes.
 __global__ void reset_queues(const uint32_t* __restrict__ init, uint32_t* __restrict__ live) {
-  if (threadIdx.x < 2 * kXcds) live[threadIdx.x] = init[threadIdx.x];
+  const int t = threadIdx.x;
+  if (t < kXcds) {
+    live[t * kHeadStride] = init[t * kHeadStride];
+    live[kEndOffset + t] = init[kEndOffset + t];
+  }
 }
 
 // Work list order: one queue per XCD (head bh belongs to XCD bh % kXcds, so the workgroups of
@@ -177,9 +187,9 @@ __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __res
   __syncthreads();
   if (tid < kXcds) {
     const uint32_t begin = bins[tid * per_xcd];
-    queues[tid] = begin;                                    // queue head
-    if (tid > 0) queues[kXcds + tid - 1] = begin;           // previous queue's end
-    if (tid == kXcds - 1) queues[2 * kXcds - 1] = (uint32_t)N;
+    queues[tid * kHeadStride] = begin;                      // queue head
+    if (tid > 0) queues[kEndOffset + tid - 1] = begin;      // previous queue's end
+    if (tid == kXcds - 1) queues[kEndOffset + kXcds - 1] = (uint32_t)N;
   }
   __syncthreads();
   for (int r = tid; r < N; r += kOrderThreads) {
@@ -273,23 +283,26 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
   // This workgroup's home queue is the one of the XCD it runs on (hardware register XCC_ID).
   const int my_q = (int)(__builtin_amdgcn_s_getreg(kHwRegXccId) & 15u) % kXcds;
   uint32_t* const q_head = p.queues;
-  const uint32_t* const q_end = p.queues + kXcds;
+  const uint32_t* const q_end = p.queues + kEndOffset;
 
-  for (;;) {
+  // The item number reaches the other waves through one of two LDS slots, used in turn: a wave reads slot s of
+  // item i before it arrives at the barrier of item i + 1, and the slot is not written again before that barrier
+  // has been passed, so one barrier per item is enough.  The barrier waits for LDS traffic only; __syncthreads()
+  // would also make every wave wait for the acknowledgement of its stores of the previous item.
+  for (int parity = 0;; parity ^= 1) {
     if (tid == 0) {
       // next item of the home queue; when that is drained, steal from the other XCDs' queues
       int item = -1;
       for (int k = 0; k < kXcds && item < 0; ++k) {
         const int q = (my_q + k) % kXcds;
         const uint32_t end = q_end[q];
-        if (__hip_atomic_load(q_head + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= end) continue;
-        const uint32_t got = atomicAdd(q_head + q, 1u);
+        const uint32_t got = atomicAdd(q_head + q * kHeadStride, 1u);   // a drained queue just keeps counting
         if (got < end) item = (int)got;
       }
-      s_item[0] = item;
+      s_item[parity] = item;
     }
-    __syncthreads();
-    const int n = __builtin_amdgcn_readfirstlane(s_item[0]);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    const int n = __builtin_amdgcn_readfirstlane(s_item[parity]);
     if (n < 0) break;
     const uint32_t entry = p.order[n];
     const int row = (int)(entry & ~kCopyFlag);
@@ -328,7 +341,6 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
 #pragma unroll 4
         for (int t = tid; t < NV; t += NT) dst[t] = src[t];
       }
-      __syncthreads();
       continue;
     }
 
@@ -621,7 +633,6 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
           if (row_exists) *(u32x2*)(orow + (32 * db + 8 * q4 + 4 * half) * 2) = pk;
         }
     }
-    __syncthreads();
   }
 }
 
@@ -674,10 +685,11 @@ int check_shape(int B, int H, int L, int D, int bq, int bk, bool need_d, Shape* 
   return 0;
 }
 
-// scratch layout: [queue heads and ends (256 B)] [order N u32] [keys N i32] [words N*nw32 u32]
+// scratch layout: [queue heads and ends (kQueueBytes)] [order N u32] [keys N i32] [words N*nw32 u32]
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+constexpr size_t kQueueBytes = (size_t)kQueueWords * 4;
 size_t workspace_bytes(const Shape& s) {
-  return 256 + align256((size_t)s.N * 4) * 2 + align256((size_t)s.N * s.nw32 * 4);
+  return kQueueBytes + align256((size_t)s.N * 4) * 2 + align256((size_t)s.N * s.nw32 * 4);
 }
 
 struct Scratch {
@@ -747,7 +759,7 @@ int launch_attn(const AttnParams& p, int grid, hipStream_t stream) {
 }
 
 struct PlanBuffers {
-  uint32_t* queues;   // kXcds live queue heads, then kXcds queue ends
+  uint32_t* queues;   // live queue heads and ends (kQueueWords)
   uint32_t* order;    // [N]
   int32_t* keys;      // [N]
   uint32_t* words;    // [N][nw32]
@@ -756,9 +768,9 @@ struct PlanBuffers {
 PlanBuffers carve(char* base, const Shape& s) {
   PlanBuffers b;
   b.queues = (uint32_t*)base;
-  b.order = (uint32_t*)(base + 256);
-  b.keys = (int32_t*)(base + 256 + align256((size_t)s.N * 4));
-  b.words = (uint32_t*)(base + 256 + 2 * align256((size_t)s.N * 4));
+  b.order = (uint32_t*)(base + kQueueBytes);
+  b.keys = (int32_t*)(base + kQueueBytes + align256((size_t)s.N * 4));
+  b.words = (uint32_t*)(base + kQueueBytes + 2 * align256((size_t)s.N * 4));
   return b;
 }
 
@@ -769,7 +781,7 @@ struct sparse_attn_plan {
   Shape s;
   int gran;
   int dev;
-  void* mem;               // [initial queue heads and ends (256 B)] [workspace as carved above]
+  void* mem;               // [initial queue heads and ends (kQueueBytes)] [workspace as carved above]
   uint32_t* queues_init;
   PlanBuffers bufs;
 };
@@ -969,13 +981,13 @@ int sparse_attn_plan_create(const uint8_t* cache_flags, const uint8_t* kv_mask, 
   pl->gran = granularity;
   pl->mem = nullptr;
   hipError_t e = hipGetDevice(&pl->dev);
-  if (e == hipSuccess) e = hipMalloc(&pl->mem, 256 + workspace_bytes(s));
+  if (e == hipSuccess) e = hipMalloc(&pl->mem, kQueueBytes + workspace_bytes(s));
   if (e != hipSuccess) {
     delete pl;
     return fail(SPARSE_ATTN_ERR_HIP, "plan allocation failed: %s", hipGetErrorString(e));
   }
   pl->queues_init = (uint32_t*)pl->mem;
-  pl->bufs = carve((char*)pl->mem + 256, s);
+  pl->bufs = carve((char*)pl->mem + kQueueBytes, s);
   if (int rc = launch_plan(cache_flags, kv_mask, s, granularity, pl->bufs, pl->queues_init, (hipStream_t)hip_stream)) {
     (void)hipFree(pl->mem);
     delete pl;
