@@ -352,18 +352,8 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     // Q fragment: B operand of S^T = K Q^T; lane holds query row l32, d = 16*ks + 8*half .. +7.
     // It is multiplied by log2(e)/sqrt(D) once here (rounded back to bf16), so the MFMA result is
     // already the exponent of 2 and the softmax needs no multiply per score.
+    // (It is loaded further down, behind the first K/V sub-tile's loads, so that the two latencies overlap.)
     bf16x8 qf[KS];
-    {
-      int qr = wave * 32 + l32;
-      if constexpr (RAGGED) qr = min(qr, p.L - 1 - iq * BQ);
-      const char* qrow = p.Q + blk_off + (size_t)qr * ROWB + half * 16;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 q = *(const bf16x8*)(qrow + ks * 32);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qf[ks][e] = (__bf16)((float)q[e] * c);
-      }
-    }
 
     f32x16 o[DB];
 #pragma unroll
@@ -588,6 +578,17 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     int j = next_block();
     int sub = 0;
     if (j >= 0) issue_loads(j, 0, Buf0{}, 0, NLOAD);
+    {
+      int qr = wave * 32 + l32;
+      if constexpr (RAGGED) qr = min(qr, p.L - 1 - iq * BQ);
+      const char* qrow = p.Q + blk_off + (size_t)qr * ROWB + half * 16;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 q = *(const bf16x8*)(qrow + ks * 32);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[ks][e] = (__bf16)((float)q[e] * c);
+      }
+    }
     auto step = [&](auto cur, auto other) {
       int nj = j, nsub = sub + 1;
       if constexpr (RAGGED) {
