@@ -37,6 +37,19 @@ def test_short_last_blocks_match_oracle(D, bq, bk, L):
     check_against_oracle(w, got, ref, ref_bits, f"ragged dense D{D} {bq}x{bk} L{L}")
 
 
+@pytest.mark.parametrize("D,blk,L", [(64, 64, 1), (64, 64, 7), (64, 64, 65), (128, 128, 1), (128, 128, 31), (128, 128, 129)])
+def test_one_head_of_a_handful_of_tokens(D, blk, L):
+    """One or two work items in all: seven of the eight work queues are empty from the start, the single token of
+    L = 1 attends to itself (O = V)."""
+    print(f"[case] tiny D={D} {blk}x{blk} L={L}", flush=True)
+    w = synth.random_case(synth.BASE_SEED + 300 + L, 1, 1, L, D, blk, blk, keep=1.0, cached_frac=0.0)
+    got = DeviceCase(w).run()
+    ref, ref_bits = oracle_full(w)
+    check_against_oracle(w, got, ref, ref_bits, f"tiny D{D} L{L}")
+    if L == 1:
+        assert (got == w.V).all()
+
+
 def test_nothing_past_the_end_is_read_or_written():
     """One head whose tensors sit at the start of larger buffers: NaN behind Q, K, V and the cache, a marker
     behind O.  A read past the end would put NaN into the result (0 * NaN), a write would change the marker."""
