@@ -81,6 +81,27 @@ int sparse_attn_fwd_stream(const void* Q, const void* K, const void* V,
                            void* hip_stream);
 
 /*
+ * sparse_attn_fwd_stream for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same output bits; the symbol
+ * pre-pass (queue counters, work list, kept counts, decoded symbol words) lives in a fixed array of
+ * SPARSE_ATTN_NOALLOC_SCRATCH_BYTES bytes inside the library's device image instead of an allocated buffer.
+ * The call allocates and frees nothing, on the host side of HIP or on the device.
+ *   - A shape is accepted iff sparse_attn_workspace_bytes(B, H, L, block_q, block_k) fits in the array
+ *     (about 4 * B*H*Tq * (ceil(Tkv/32) + 2) bytes: 0.27 MiB at B=1, H=24, L=33024 with 128 x 128 blocks);
+ *     anything larger returns SPARSE_ATTN_ERR_UNSUPPORTED with a message that names both sizes.
+ *   - Every GPU the library runs on holds its own copy of the array until the process ends.  All calls on a
+ *     GPU share it, whatever their stream: two calls that overlap in time on one GPU race and give wrong
+ *     results.  Calls on one stream, or otherwise ordered, are fine; the array keeps the previous call's
+ *     contents and every word a call reads is written by that call's own pre-pass first.
+ */
+#define SPARSE_ATTN_NOALLOC_SCRATCH_BYTES ((size_t)2 << 20)
+int sparse_attn_fwd_noalloc(const void* Q, const void* K, const void* V,
+                            const uint8_t* cache_flags, const uint8_t* kv_mask,
+                            const void* O_cache, void* O,
+                            int B, int H, int L, int D, int block_q, int block_k,
+                            void* hip_stream);
+
+/*
  * Measurement variant: same work as sparse_attn_fwd_stream, bracketed by HIP events on the
  * given stream, synchronised before returning.  plan_ms (host, may be NULL) receives the
  * duration of the symbol pre-pass (decode, count and ordering of work items), attn_ms (host,

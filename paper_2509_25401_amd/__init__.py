@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     sparse_attn_fwd,
+    sparse_attn_fwd_noalloc,
     sparse_attn_fwd_timed,
     sparse_gemm_q,
     sparse_gemm_o,

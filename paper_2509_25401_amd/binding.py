@@ -40,6 +40,8 @@ def load_library():
     lib.sparse_attn_fwd.restype = i32
     lib.sparse_attn_fwd_stream.argtypes = fwd_args + [vp]
     lib.sparse_attn_fwd_stream.restype = i32
+    lib.sparse_attn_fwd_noalloc.argtypes = fwd_args + [vp]
+    lib.sparse_attn_fwd_noalloc.restype = i32
     lib.sparse_attn_fwd_timed.argtypes = fwd_args + [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
     lib.sparse_attn_fwd_timed.restype = i32
     lib.sparse_attn_workspace_bytes.argtypes = [i32] * 5
@@ -142,6 +144,15 @@ def sparse_attn_fwd(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k,
     """
     args = _fwd_args(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k)
     rc = load_library().sparse_attn_fwd_stream(*args, _stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
+    return O
+
+
+def sparse_attn_fwd_noalloc(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k, stream=None):
+    """sparse_attn_fwd through the entry point that allocates nothing (fixed scratch inside the library)."""
+    args = _fwd_args(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k)
+    rc = load_library().sparse_attn_fwd_noalloc(*args, _stream_ptr(stream))
     if rc != 0:
         _raise(rc)
     return O

@@ -702,6 +702,37 @@ std::map<std::pair<int, void*>, Scratch> g_scratch;
 
 }  // namespace
 
+// Scratch of the entry point that allocates nothing: every GPU the library runs on holds its own copy of this
+// array for the life of the process.  In host code the name is only a handle for hipGetSymbolAddress; kernels
+// and copies use the per-device address that call returns.
+constexpr size_t kStaticScratchBytes = SPARSE_ATTN_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_static_scratch[kMaxDevices] = {};
+
+// Address of `scratch` on the current device, looked up once per device.
+int static_scratch_ptr(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "device index %d is out of range", dev);
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (!g_static_scratch[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return sa_fail(SPARSE_ATTN_ERR_HIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+    g_static_scratch[dev] = ptr;
+  }
+  *out = g_static_scratch[dev];
+  return 0;
+}
+
+}  // namespace
+
 int sa_get_scratch(size_t need, hipStream_t stream, void** out) {
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev));
@@ -817,7 +848,8 @@ struct Forecast {
 
 int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags, const uint8_t* kv_mask,
         const void* O_cache, void* O, int B, int H, int L, int D, int bq, int bk, hipStream_t stream, float* plan_ms,
-        float* attn_ms, bool timed, const Forecast* fc = nullptr, const sparse_attn_plan* plan = nullptr) {
+        float* attn_ms, bool timed, const Forecast* fc = nullptr, const sparse_attn_plan* plan = nullptr,
+        bool static_scratch = false) {
   Shape s;
   if (int rc = check_shape(B, H, L, D, bq, bk, true, &s)) return rc;
   if (!Q || !K || !V || !O) return fail(SPARSE_ATTN_ERR_INVALID, "Q, K, V and O must not be NULL");
@@ -844,6 +876,15 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
   PlanBuffers pb;
   if (plan) {
     pb = plan->bufs;
+  } else if (static_scratch) {
+    const size_t need = workspace_bytes(s);
+    if (need > kStaticScratchBytes)
+      return fail(SPARSE_ATTN_ERR_UNSUPPORTED,
+                  "this shape needs %zu bytes of scratch, the no-allocation entry point holds %zu "
+                  "(B*H*Tq*(ceil(Tkv/32)+2)*4 bytes must fit)", need, kStaticScratchBytes);
+    void* ws = nullptr;
+    if (int rc = static_scratch_ptr(&ws)) return rc;
+    pb = carve((char*)ws, s);
   } else {
     void* ws = nullptr;
     if (int rc = sa_get_scratch(workspace_bytes(s), stream, &ws)) return rc;
@@ -958,6 +999,13 @@ int sparse_attn_fwd_timed(const void* Q, const void* K, const void* V, const uin
                           int block_q, int block_k, void* hip_stream, float* plan_ms, float* attn_ms) {
   return run(Q, K, V, cache_flags, kv_mask, O_cache, O, B, H, L, D, block_q, block_k, (hipStream_t)hip_stream,
              plan_ms, attn_ms, true);
+}
+
+int sparse_attn_fwd_noalloc(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
+                            const uint8_t* kv_mask, const void* O_cache, void* O, int B, int H, int L, int D,
+                            int block_q, int block_k, void* hip_stream) {
+  return run(Q, K, V, cache_flags, kv_mask, O_cache, O, B, H, L, D, block_q, block_k, (hipStream_t)hip_stream,
+             nullptr, nullptr, false, nullptr, nullptr, true);
 }
 
 int sparse_attn_fwd_forecast(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,

@@ -57,6 +57,18 @@ def test_argument_validation_precedes_any_device_work(kw, code):
     assert pkg.sparse_attn_last_error() != ""
 
 
+def test_no_alloc_entry_point_rejects_shapes_beyond_its_scratch():
+    """The size check precedes every HIP call: B*H*Tq = 64*64*256 rows of 8 + 2 words need 40 MiB, the fixed array
+    holds 2 MiB."""
+    lib = pkg.load_library()
+    assert pkg.sparse_attn_workspace_bytes(64, 64, 32768, 128, 128) > (2 << 20)
+    far = [ctypes.c_void_p(0x10000 + k * (1 << 40)) for k in range(4)]
+    rc = lib.sparse_attn_fwd_noalloc(far[0], far[1], far[2], None, None, None, far[3], 64, 64, 32768, 128, 128, 128, None)
+    assert rc == -2 and "scratch" in pkg.sparse_attn_last_error()
+    # validation of the ordinary arguments is shared with the other entry points
+    assert lib.sparse_attn_fwd_noalloc(None, far[1], far[2], None, None, None, far[3], 1, 1, 128, 128, 128, 128, None) == -1
+
+
 def test_workspace_bytes():
     assert pkg.sparse_attn_workspace_bytes(1, 24, 33024, 128, 128) >= 24 * 258 * (4 + 4 + 9 * 4)
     assert pkg.sparse_attn_workspace_bytes(1, 24, 33024, 128, 128) < 1 << 20
