@@ -87,7 +87,7 @@ int sparse_attn_fwd_stream(const void* Q, const void* K, const void* V,
  * SPARSE_ATTN_NOALLOC_SCRATCH_BYTES bytes inside the library's device image instead of an allocated buffer.
  * The call allocates and frees nothing, on the host side of HIP or on the device.
  *   - A shape is accepted iff sparse_attn_workspace_bytes(B, H, L, block_q, block_k) fits in the array
- *     (about 4 * B*H*Tq * (ceil(Tkv/32) + 2) bytes: 0.27 MiB at B=1, H=24, L=33024 with 128 x 128 blocks);
+ *     (about 4 * B*H*Tq * (ceil(Tkv/32) + 3) bytes: 0.3 MiB at B=1, H=24, L=33024 with 128 x 128 blocks);
  *     anything larger returns SPARSE_ATTN_ERR_UNSUPPORTED with a message that names both sizes.
  *   - Every GPU the library runs on holds its own copy of the array until the process ends.  All calls on a
  *     GPU share it, whatever their stream: two calls that overlap in time on one GPU race and give wrong

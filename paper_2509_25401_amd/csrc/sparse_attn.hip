@@ -2,8 +2,8 @@
 //
 // Three kernels per call, all on the caller's stream:
 //   plan_rows   decodes the packed symbols of Section 3.3 once per (b,h,i) row into aligned
-//               32-bit words (bit j of the row = key block j, padding cleared) and counts the
-//               kept key blocks of every non-cached row;
+//               32-bit words (bit j of the row = key block j, padding cleared), counts the
+//               kept key blocks of every non-cached row and notes the first of them;
 //   plan_order  sorts the rows into one work queue per XCD (a head's rows all go to one XCD, so
 //               its K/V stream through one L2): heaviest rows first (16 kept-count buckets), rows
 //               of one head adjacent inside a bucket, cached rows (plain copies) last;
@@ -22,7 +22,11 @@
 //               vector instructions of the softmax sit between matrix instructions that do not
 //               depend on them (weights of one 32-key block under the scores of the next and
 //               under the O^T product of the previous), where they issue in the shadow of the
-//               wave's own MFMAs.  A copy item moves one cached block O_cache -> O.
+//               wave's own MFMAs.  The finished block leaves through LDS as whole rows.  The ticket
+//               of the next item is drawn a few key blocks before the current one ends, and its
+//               work-list entry names the first kept key block, so that tile is requested before
+//               the row's symbol words are touched.  A copy item moves one cached block
+//               O_cache -> O.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdarg.h>
@@ -77,7 +81,7 @@ struct AttnParams {
   const char* O_cache;
   char* O;
   const uint32_t* words;   // [N][nw32] decoded symbol words
-  const uint32_t* order;   // [N] work list: row | kCopyFlag
+  const uint32_t* order;   // [N][2] work list: {row | kCopyFlag, sort key of the row (see plan_rows)}
   uint32_t* queues;        // kXcds queue heads at [q * kHeadStride], kXcds queue ends at [kEndOffset + q]
   int N;                   // B*H*Tq
   int Tq;
@@ -106,7 +110,7 @@ __global__ void __launch_bounds__(256) plan_rows(const uint8_t* __restrict__ cac
   const int bh = row / Tq;
   const size_t sym_row = (size_t)bh * sym_Tq + (row - bh * Tq) / gran;
   const bool cached = cache_flags != nullptr && cache_flags[sym_row] != 0;
-  int count = 0;
+  int count = 0, first_kept = -1;
   const uint8_t* src = kv_mask ? kv_mask + sym_row * sym_row_bytes : nullptr;
   for (int w = 0; w < nw32; ++w) {
     uint32_t word = 0;
@@ -129,8 +133,10 @@ __global__ void __launch_bounds__(256) plan_rows(const uint8_t* __restrict__ cac
     }
     words[(size_t)row * nw32 + w] = word;
     count += __popc(word);
+    if (first_kept < 0 && word != 0u) first_kept = 32 * w + __ffs(word) - 1;
   }
-  keys[row] = cached ? -1 : count;
+  // key of a computed row: kept blocks in the low 16 bits (0 .. 32768), first kept block above them
+  keys[row] = cached ? -1 : (count | (max(first_kept, 0) << 16));
 }
 
 // Copies the initial queue heads and ends of a stored plan into the live ones its next run consumes.
@@ -148,7 +154,7 @@ __global__ void reset_queues(const uint32_t* __restrict__ init, uint32_t* __rest
 // head adjacent inside a bucket, cached rows (plain copies) last.
 __device__ inline int order_bin(int key, int row, int Tq, int Tkv, int shift, int groups) {
   const int bh = row / Tq;
-  const int major = key < 0 ? kBuckets : (kBuckets - 1) - (int)(((long long)key * kBuckets) / (Tkv + 1));
+  const int major = key < 0 ? kBuckets : (kBuckets - 1) - (int)(((long long)(key & 0xffff) * kBuckets) / (Tkv + 1));
   return ((bh % kXcds) * (kBuckets + 1) + major) * groups + ((bh / kXcds) >> shift);
 }
 
@@ -195,8 +201,38 @@ __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __res
   for (int r = tid; r < N; r += kOrderThreads) {
     const int key = keys[r];
     const uint32_t pos = atomicAdd(&bins[order_bin(key, r, Tq, Tkv, shift, groups)], 1u);
-    order[pos] = (uint32_t)r | (key < 0 ? kCopyFlag : 0u);
+    order[2 * pos] = (uint32_t)r | (key < 0 ? kCopyFlag : 0u);
+    order[2 * pos + 1] = (uint32_t)key;
   }
+}
+
+// One atomic increment per wave, issued by lane 0 only and left in flight: returns a register whose lane 0
+// will hold the counter's previous value.  Written as assembly around an exec-mask switch, not as
+// `if (lane == 0) atomicAdd(...)`: a value that stays live across loop iterations inside a lane-dependent
+// branch makes the compiler treat the whole scheduling state of the kernel as lane-dependent.
+__device__ __forceinline__ unsigned sa_lane0_atomic_inc(uint32_t* counter) {
+  unsigned old;
+  unsigned long long saved;
+  asm volatile(
+      "s_mov_b64 %1, exec\n\ts_mov_b64 exec, 1\n\tglobal_atomic_add %0, %2, %3, %4 sc0\n\ts_mov_b64 exec, %1"
+      : "=&v"(old), "=&s"(saved)
+      : "v"(0u), "v"(1u), "s"(counter)
+      : "memory");
+  return old;
+}
+// Waits for this wave's outstanding memory operations and returns lane 0 of `v` as a wave-uniform value.
+__device__ __forceinline__ unsigned sa_lane0_value(unsigned v) {
+  unsigned r;
+  asm volatile("s_waitcnt vmcnt(0)\n\tv_readfirstlane_b32 %0, %1" : "=s"(r) : "v"(v) : "memory");
+  return r;
+}
+// A work-list entry (two words) read with one scalar load instead of a vector load and a lane broadcast.  Load and
+// wait are one statement on purpose: the compiler does not know that the result arrives late and may copy the
+// registers in between.
+__device__ __forceinline__ unsigned long long sa_scalar_load_b64(const uint32_t* ptr) {
+  unsigned long long v;
+  asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(ptr) : "memory");
+  return v;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -241,7 +277,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   char* const ldsK = smem;                 // two K sub-tiles, then two V sub-tiles
   char* const ldsV = smem + 2 * TILEB;
-  volatile int* const s_item = (volatile int*)(smem + 4 * TILEB);
+  LDS_PTR(volatile int) const s_item = (LDS_PTR(volatile int))(smem + 4 * TILEB);
   const unsigned lds_base = (unsigned)(uintptr_t)(LDS_PTR(char))smem;
 
   const int tid = threadIdx.x;
@@ -285,26 +321,43 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
   uint32_t* const q_head = p.queues;
   const uint32_t* const q_end = p.queues + kEndOffset;
 
-  // The item number reaches the other waves through one of two LDS slots, used in turn: a wave reads slot s of
-  // item i before it arrives at the barrier of item i + 1, and the slot is not written again before that barrier
-  // has been passed, so one barrier per item is enough.  The barrier waits for LDS traffic only; __syncthreads()
-  // would also make every wave wait for the acknowledgement of its stores of the previous item.
+  // Work acquisition.  The ticket of the next item is one atomic on the home queue, issued by wave 0 and left in
+  // flight; it is drawn a few kept blocks before the current item ends (earlier would let an idle workgroup find
+  // the queue empty while this one still sits on an item it has not started), so at the end of the item it has
+  // long arrived.  The item number reaches the other waves through one of two LDS slots, used in turn: a wave
+  // reads slot s of item i before it arrives at the barrier of item i + 1, and the slot is not written again
+  // before that barrier has been passed, so one barrier per item is enough.  The barrier waits for LDS traffic
+  // only; __syncthreads() would also make every wave wait for the acknowledgement of its stores of the previous
+  // item.  The work-list entry then comes through the scalar cache and carries the row's kept-block count and
+  // first kept block, so the first K/V sub-tile is requested before the row's symbol words have been looked at.
+  constexpr int kDrawTiles = 6;        // kept blocks an item still has to visit when the next ticket is drawn
+  bool drawn = false;
+  unsigned ticket = 0;                 // wave 0: lane 0 holds the ticket of the home queue, possibly still in flight
+  auto draw_issue = [&]() {
+    if (wave == 0) ticket = sa_lane0_atomic_inc(q_head + my_q * kHeadStride);   // a drained queue just keeps counting
+    drawn = true;
+  };
   for (int parity = 0;; parity ^= 1) {
-    if (tid == 0) {
-      // next item of the home queue; when that is drained, steal from the other XCDs' queues
-      int item = -1;
-      for (int k = 0; k < kXcds && item < 0; ++k) {
+    if (!drawn) draw_issue();
+    drawn = false;
+    if (wave == 0) {
+      // resolve the ticket; when the home queue is drained, steal from the other XCDs' queues
+      const uint32_t t = sa_lane0_value(ticket);
+      int item = t < q_end[my_q] ? (int)t : -1;
+      for (int k = 1; k < kXcds && item < 0; ++k) {
         const int q = (my_q + k) % kXcds;
         const uint32_t end = q_end[q];
-        const uint32_t got = atomicAdd(q_head + q * kHeadStride, 1u);   // a drained queue just keeps counting
+        const uint32_t got = sa_lane0_value(sa_lane0_atomic_inc(q_head + q * kHeadStride));
         if (got < end) item = (int)got;
       }
-      s_item[parity] = item;
+      s_item[parity] = item;           // every lane writes the same value
     }
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     const int n = __builtin_amdgcn_readfirstlane(s_item[parity]);
     if (n < 0) break;
-    const uint32_t entry = p.order[n];
+    const unsigned long long entry64 = sa_scalar_load_b64(p.order + 2 * (size_t)n);
+    const uint32_t entry = (uint32_t)entry64;
+    const uint32_t key = (uint32_t)(entry64 >> 32);
     const int row = (int)(entry & ~kCopyFlag);
     const int bh = row / p.Tq;
     const int iq = row - bh * p.Tq;
@@ -372,14 +425,20 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     bool first = true;
     float l_run = 0.f;   // per-lane partial row sum (this lane's half of the keys)
 
-    // scalar walk over the set bits of the decoded symbol row
-    int w_idx = 0;
-    uint32_t w_bits = wp[0];
+    // Scalar walk over the set bits of the decoded symbol row.  The row's words sit one per lane in a vector
+    // register (one coalesced load per item, 64 words at a time), so moving on to the next word is a lane read,
+    // not a memory access.
+    int tiles_left = (int)(key & 0xffffu);          // kept blocks not yet visited, the current one included
+    int w_idx = (int)(key >> 21);                    // word of the first kept block
+    auto load_words = [&](int w0) -> uint32_t { return w0 + lane < p.nw32 ? wp[w0 + lane] : 0u; };
+    uint32_t w_lanes = load_words(w_idx & ~63);
+    uint32_t w_bits = 0;
     auto next_block = [&]() -> int {
       while (w_bits == 0u) {
         ++w_idx;
         if (w_idx >= p.nw32) return -1;
-        w_bits = wp[w_idx];
+        if ((w_idx & 63) == 0) w_lanes = load_words(w_idx);
+        w_bits = (uint32_t)__builtin_amdgcn_readlane((int)w_lanes, w_idx & 63);
       }
       const int b = __builtin_ctz(w_bits);
       w_bits &= w_bits - 1u;
@@ -575,7 +634,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     // the loads of sub-tile u+1 are in flight into the other.
     using Buf0 = std::integral_constant<int, 0>;
     using Buf1 = std::integral_constant<int, 1>;
-    int j = next_block();
+    int j = tiles_left > 0 ? (int)(key >> 16) : -1;
     int sub = 0;
     if (j >= 0) issue_loads(j, 0, Buf0{}, 0, NLOAD);
     {
@@ -589,6 +648,9 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
         for (int e = 0; e < 8; ++e) qf[ks][e] = (__bf16)((float)q[e] * c);
       }
     }
+    // the walk continues behind the first kept block
+    if (j >= 0) w_bits = (uint32_t)__builtin_amdgcn_readlane((int)w_lanes, w_idx & 63) & ~((2u << (j & 31)) - 1u);
+    if (tiles_left <= kDrawTiles) draw_issue();
     auto step = [&](auto cur, auto other) {
       int nj = j, nsub = sub + 1;
       if constexpr (RAGGED) {
@@ -597,6 +659,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       if (nsub == SUB) {
         nsub = 0;
         nj = next_block();
+        if (--tiles_left == kDrawTiles) draw_issue();
       }
       sa_wait_vmem();
       __syncthreads();   // this sub-tile has landed for every wave; the other buffer is free
@@ -604,20 +667,34 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       j = nj;
       sub = nsub;
     };
+    int last = 0;     // buffer of the last sub-tile
     while (j >= 0) {
       step(Buf0{}, Buf1{});
+      last = 0;
       if (j < 0) break;
       step(Buf1{}, Buf0{});
+      last = 1;
     }
 
-    // O_i = diag(l)^-1 O_acc; both lane halves hold partial sums of the same row
+    // O_i = diag(l)^-1 O_acc; both lane halves hold partial sums of the same row.  A lane owns one query row, so
+    // stored straight from the accumulators every store instruction would touch 32 rows with 16 bytes each; the
+    // block goes through LDS instead and leaves as whole rows, 16 bytes per lane.  The staging area is the buffer
+    // that the last sub-tile did NOT use: nothing was fetched into it meanwhile and every wave has finished
+    // reading it (it passed the barrier of the last sub-tile after that); each wave stages its own 32 rows, so
+    // no barrier is needed here, and the barrier at the top of the next item comes before anything is fetched
+    // into that buffer again.
     {
       const unsigned bits = __builtin_bit_cast(unsigned, l_run);
       const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
       const float l_tot = __builtin_bit_cast(float, (unsigned)sw[0]) + __builtin_bit_cast(float, (unsigned)sw[1]);
       const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-      char* orow = p.O + blk_off + (size_t)(wave * 32 + l32) * ROWB;
-      const bool row_exists = !RAGGED || iq * BQ + wave * 32 + l32 < p.L;
+      char* const stage = (wave < 2 ? ldsK : ldsV) + (last ^ 1) * TILEB + (wave & 1) * 32 * ROWB;
+      // (the lane number passes through an empty asm statement: otherwise the two dozen lane-dependent offsets
+      // below are computed once, in front of the item loop, and occupy registers for the whole kernel)
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      const int srow = ln & 31;
+      char* const wr = stage + srow * ROWB + (ln >> 5) * 8;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -631,8 +708,18 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
           u32x2 pk;
           pk[0] = __builtin_bit_cast(unsigned, lo);
           pk[1] = __builtin_bit_cast(unsigned, hi);
-          if (row_exists) *(u32x2*)(orow + (32 * db + 8 * q4 + 4 * half) * 2) = pk;
+          // 16-byte chunks of a row permuted by the row, so that the 32 rows of one write fall into distinct banks
+          *(u32x2*)(wr + (((4 * db + q4) ^ (srow & (CH - 1))) * 16)) = pk;
         }
+      constexpr int RPI = 1024 / ROWB;       // rows per store instruction
+      char* const obase = p.O + blk_off + (size_t)(wave * 32) * ROWB;
+      const int rows_here = RAGGED ? p.L - (iq * BQ + wave * 32) : 32;   // rows of this wave's slab that exist
+#pragma unroll
+      for (int t = 0; t < 32 / RPI; ++t) {
+        const int r = t * RPI + ln / CH, ch = ln % CH;
+        const u32x4 v = *(const u32x4*)(stage + r * ROWB + ((ch ^ (r & (CH - 1))) * 16));
+        if (!RAGGED || r < rows_here) *(u32x4*)(obase + r * ROWB + ch * 16) = v;
+      }
     }
   }
 }
@@ -686,11 +773,11 @@ int check_shape(int B, int H, int L, int D, int bq, int bk, bool need_d, Shape* 
   return 0;
 }
 
-// scratch layout: [queue heads and ends (kQueueBytes)] [order N u32] [keys N i32] [words N*nw32 u32]
+// scratch layout: [queue heads and ends (kQueueBytes)] [order N x 2 u32] [keys N i32] [words N*nw32 u32]
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 constexpr size_t kQueueBytes = (size_t)kQueueWords * 4;
 size_t workspace_bytes(const Shape& s) {
-  return kQueueBytes + align256((size_t)s.N * 4) * 2 + align256((size_t)s.N * s.nw32 * 4);
+  return kQueueBytes + align256((size_t)s.N * 8) + align256((size_t)s.N * 4) + align256((size_t)s.N * s.nw32 * 4);
 }
 
 struct Scratch {
@@ -792,7 +879,7 @@ int launch_attn(const AttnParams& p, int grid, hipStream_t stream) {
 
 struct PlanBuffers {
   uint32_t* queues;   // live queue heads and ends (kQueueWords)
-  uint32_t* order;    // [N]
+  uint32_t* order;    // [N][2]
   int32_t* keys;      // [N]
   uint32_t* words;    // [N][nw32]
 };
@@ -801,8 +888,8 @@ PlanBuffers carve(char* base, const Shape& s) {
   PlanBuffers b;
   b.queues = (uint32_t*)base;
   b.order = (uint32_t*)(base + kQueueBytes);
-  b.keys = (int32_t*)(base + kQueueBytes + align256((size_t)s.N * 4));
-  b.words = (uint32_t*)(base + kQueueBytes + 2 * align256((size_t)s.N * 4));
+  b.keys = (int32_t*)(base + kQueueBytes + align256((size_t)s.N * 8));
+  b.words = (uint32_t*)(base + kQueueBytes + align256((size_t)s.N * 8) + align256((size_t)s.N * 4));
   return b;
 }
 
@@ -881,7 +968,7 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
     if (need > kStaticScratchBytes)
       return fail(SPARSE_ATTN_ERR_UNSUPPORTED,
                   "this shape needs %zu bytes of scratch, the no-allocation entry point holds %zu "
-                  "(B*H*Tq*(ceil(Tkv/32)+2)*4 bytes must fit)", need, kStaticScratchBytes);
+                  "(B*H*Tq*(ceil(Tkv/32)+3)*4 bytes must fit)", need, kStaticScratchBytes);
     void* ws = nullptr;
     if (int rc = static_scratch_ptr(&ws)) return rc;
     pb = carve((char*)ws, s);
