@@ -136,15 +136,6 @@ int sparse_gemm_q_stream(const void* X, const void* W, const void* bias, const u
                          int B, int L, int C, int H, int D, int block_q, void* hip_stream);
 
 /*
- * Measurement helper (not part of the method; the callers it is for are benchmarks): the bf16 MFMA rate the
- * current device sustains on a loop of nothing but v_mfma_f32_32x32x16_bf16, two waves per SIMD, with constant
- * (random_operands = 0) or random (1) operand data.  Runs `launches` (1..64) launches of about 10 ms on the null
- * stream, synchronises, and reports the last one: *tflops (host) and, if not NULL, *shader_mhz (host), the shader
- * clock during that launch.  Allocates and frees a few hundred KB of device memory.  Errors as for sparse_attn_fwd.
- */
-int sparse_attn_probe_mfma(int random_operands, int launches, double* tflops, double* shader_mhz);
-
-/*
  * Reusable plan (Section 3.2: symbols are refreshed at an Update step and then drive the following Dispatch
  * steps unchanged; Section 3.3: one symbol may cover n x n tiles).  sparse_attn_plan_create runs the
  * symbol pre-pass once -- decode of S_c and S_s, kept-pair counts, the ordered work list -- and keeps its

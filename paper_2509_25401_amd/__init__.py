@@ -14,7 +14,6 @@ from .binding import (  # noqa: F401
     sparse_gemm_q,
     sparse_gemm_o,
     SparseAttnPlan,
-    sparse_attn_probe_mfma,
     sparse_gemm_q_norm_rope,
     sparse_symbols_update,
     sparse_attn_fwd_forecast,

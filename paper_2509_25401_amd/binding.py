@@ -54,8 +54,6 @@ def load_library():
     lib.sparse_gemm_q.restype = i32
     lib.sparse_gemm_q_stream.argtypes = [vp] * 5 + [i32] * 6 + [vp]
     lib.sparse_gemm_q_stream.restype = i32
-    lib.sparse_attn_probe_mfma.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
-    lib.sparse_attn_probe_mfma.restype = i32
     lib.sparse_attn_plan_create.argtypes = [vp, vp] + [i32] * 6 + [vp, ctypes.POINTER(vp)]
     lib.sparse_attn_plan_create.restype = i32
     lib.sparse_attn_plan_run.argtypes = [vp] * 6 + [i32, vp]
@@ -125,11 +123,50 @@ def _stream_ptr(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
+def _check(t, name, dtype, shape, allow_none=False):
+    """Raises ValueError unless tensor `t` has exactly this dtype and shape (the kernels index by them: a mask packed
+    for another block size, or an int32 flag tensor, would make them read past the allocation)."""
+    if t is None:
+        if allow_none:
+            return
+        raise ValueError(f"{name} must not be None")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+
+
+def _same_device(tensors):
+    devs = {str(t.device) for t in tensors if t is not None}
+    if len(devs) > 1:
+        raise ValueError(f"all tensors must live on one device, got {sorted(devs)}")
+
+
+def _ceil_div(a, b):
+    return -(-int(a) // int(b))
+
+
+def _check_attn_tensors(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k, granularity=1):
+    """Shapes and dtypes of the attention call as include/sparse_attn.h documents them."""
+    import torch
+    if Q.dim() != 4:
+        raise ValueError("Q must be [B, H, L, D]")
+    B, H, L, D = (int(x) for x in Q.shape)
+    if int(block_q) <= 0 or int(block_k) <= 0 or int(granularity) <= 0:
+        raise ValueError("block sizes and granularity must be positive")
+    Tq, Tkv = _ceil_div(L, block_q), _ceil_div(L, block_k)
+    sTq, sTkv = _ceil_div(Tq, granularity), _ceil_div(Tkv, granularity)
+    for name, t in (("Q", Q), ("K", K), ("V", V), ("O", O)):
+        _check(t, name, torch.bfloat16, (B, H, L, D))
+    _check(O_cache, "O_cache", torch.bfloat16, (B, H, L, D), allow_none=True)
+    _check(cache_flags, "cache_flags", torch.uint8, (B, H, sTq), allow_none=True)
+    _check(kv_mask, "kv_mask", torch.uint8, (B, H, sTq, _ceil_div(sTkv, 8)), allow_none=True)
+    _same_device((Q, K, V, O, O_cache, cache_flags, kv_mask))
+    return B, H, L, D
+
+
 def _fwd_args(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k):
-    B, H, L, D = Q.shape
-    for name, t in (("K", K), ("V", V), ("O", O)):
-        if tuple(t.shape) != (B, H, L, D):
-            raise ValueError(f"{name} must have the shape of Q")
+    B, H, L, D = _check_attn_tensors(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k)
     return [_dev_ptr(Q, "Q"), _dev_ptr(K, "K"), _dev_ptr(V, "V"),
             _dev_ptr(cache_flags, "cache_flags", True), _dev_ptr(kv_mask, "kv_mask", True),
             _dev_ptr(O_cache, "O_cache", True), _dev_ptr(O, "O"),
@@ -183,21 +220,21 @@ def sparse_gemm_q(X, W, bias, cache_flags, Q, block_q, stream=None):
     return Q
 
 
-def sparse_attn_probe_mfma(random_operands: bool, launches: int = 6):
-    """(TFLOP/s, shader MHz) of an MFMA-only loop on the current device (measurement helper)."""
-    tf, mhz = ctypes.c_double(0), ctypes.c_double(0)
-    rc = load_library().sparse_attn_probe_mfma(1 if random_operands else 0, int(launches), ctypes.byref(tf), ctypes.byref(mhz))
-    if rc != 0:
-        _raise(rc)
-    return tf.value, mhz.value
-
-
 class SparseAttnPlan:
     """Handle of sparse_attn_plan_create: the symbol pre-pass stored for the Dispatch steps that reuse the symbols."""
 
     def __init__(self, cache_flags, kv_mask, B, H, L, block_q, block_k, granularity=1, stream=None):
+        import torch
         self._h = ctypes.c_void_p()
         self.shape = (int(B), int(H), int(L))
+        self.blocks = (int(block_q), int(block_k))
+        if int(block_q) <= 0 or int(block_k) <= 0 or int(granularity) <= 0:
+            raise ValueError("block sizes and granularity must be positive")
+        sTq = _ceil_div(_ceil_div(L, block_q), granularity)
+        sTkv = _ceil_div(_ceil_div(L, block_k), granularity)
+        _check(cache_flags, "cache_flags", torch.uint8, (int(B), int(H), sTq), allow_none=True)
+        _check(kv_mask, "kv_mask", torch.uint8, (int(B), int(H), sTq, _ceil_div(sTkv, 8)), allow_none=True)
+        _same_device((cache_flags, kv_mask))
         rc = load_library().sparse_attn_plan_create(_dev_ptr(cache_flags, "cache_flags", True),
                                                     _dev_ptr(kv_mask, "kv_mask", True), int(B), int(H), int(L),
                                                     int(block_q), int(block_k), int(granularity), _stream_ptr(stream),
@@ -206,7 +243,7 @@ class SparseAttnPlan:
             _raise(rc)
 
     def run(self, Q, K, V, O_cache, O, stream=None):
-        B, H, L, D = Q.shape
+        B, H, L, D = _check_attn_tensors(Q, K, V, None, None, O_cache, O, *self.blocks)
         if (B, H, L) != self.shape:
             raise ValueError("Q does not have the shape the plan was made for")
         rc = load_library().sparse_attn_plan_run(self._h, _dev_ptr(Q, "Q"), _dev_ptr(K, "K"), _dev_ptr(V, "V"),
@@ -218,12 +255,12 @@ class SparseAttnPlan:
 
     def run_forecast(self, Q, K, V, O_terms, coef, O, stream=None):
         """run() with OP_reuse = sum_d coef[d] * O_terms[d] in the cache branch (see sparse_attn_fwd_forecast)."""
-        B, H, L, D = Q.shape
+        import torch
+        B, H, L, D = _check_attn_tensors(Q, K, V, None, None, None, O, *self.blocks)
         if (B, H, L) != self.shape:
             raise ValueError("Q does not have the shape the plan was made for")
-        for t in O_terms:
-            if tuple(t.shape) != (B, H, L, D):
-                raise ValueError("every term must have the shape of Q")
+        for n, t in enumerate(O_terms):
+            _check(t, f"O_terms[{n}]", torch.bfloat16, (B, H, L, D))
         ptrs, cf = _term_arrays(O_terms, coef, "O_terms")
         rc = load_library().sparse_attn_plan_run_forecast(self._h, _dev_ptr(Q, "Q"), _dev_ptr(K, "K"), _dev_ptr(V, "V"),
                                                           ptrs, cf, len(O_terms), _dev_ptr(O, "O"), int(D),
@@ -299,10 +336,10 @@ def _term_arrays(terms, coef, name):
 def sparse_attn_fwd_forecast(Q, K, V, cache_flags, kv_mask, O_terms, coef, O, block_q, block_k, stream=None):
     """Algorithm 1 with OP_reuse = sum_d coef[d] * O_terms[d] in the cache branch (Taylor forecast of cached blocks).
     O_terms: list of device tensors bf16 [B,H,L,D]; coef: list of floats (see sparse_taylor_coefficients)."""
-    B, H, L, D = Q.shape
-    for t in O_terms:
-        if tuple(t.shape) != (B, H, L, D):
-            raise ValueError("every term must have the shape of Q")
+    import torch
+    B, H, L, D = _check_attn_tensors(Q, K, V, cache_flags, kv_mask, None, O, block_q, block_k)
+    for n, t in enumerate(O_terms):
+        _check(t, f"O_terms[{n}]", torch.bfloat16, (B, H, L, D))
     ptrs, cf = _term_arrays(O_terms, coef, "O_terms")
     rc = load_library().sparse_attn_fwd_forecast(_dev_ptr(Q, "Q"), _dev_ptr(K, "K"), _dev_ptr(V, "V"),
                                                  _dev_ptr(cache_flags, "cache_flags", True),

@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRCS = [os.path.join(HERE, "csrc", n) for n in ("sparse_attn.hip", "sparse_gemm_q.hip", "sparse_gemm_o.hip", "sparse_symbols.hip", "sparse_op_reuse.hip", "probe_mfma.hip")]
+SRCS = [os.path.join(HERE, "csrc", n) for n in ("sparse_attn.hip", "sparse_gemm_q.hip", "sparse_gemm_o.hip", "sparse_symbols.hip", "sparse_op_reuse.hip")]
 LIB = os.path.join(HERE, "libsparse_attn_hip.so")
 
 

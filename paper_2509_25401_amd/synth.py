@@ -253,6 +253,31 @@ def config_video_sweep(keep: float, skewed: bool = False, H: Optional[int] = Non
                     {"text_blocks": nt, "target_keep": keep, "skewed": skewed})
 
 
+PAPER_POINTS = ("bss80", "fc80", "combined90")
+
+
+def paper_operating_point(name: str, H: Optional[int] = None):
+    """Symbols of the three operating points the paper quotes for its kernel (Section 4.3 and the attention
+    sweep of the appendix, random symbols): 'bss80' = 80 % block-sparse skipping (20 % keep, nothing cached),
+    'fc80' = 80 % of the vision query blocks cached (nothing skipped), 'combined90' = half of the vision query
+    blocks cached and the rest at 20 % keep.  Returns (M_s or None, cache_flags or None) at the video shape."""
+    s = VIDEO_SHAPE
+    B, T, nt = s["B"], s["L"] // s["block_q"], s["text_blocks"]
+    H = s["H"] if H is None else H
+    rng = np.random.default_rng(np.random.SeedSequence([BASE_SEED + 6, PAPER_POINTS.index(name)]))
+
+    def vision_flags(frac):
+        f = np.zeros((B, H, T), dtype=np.uint8)
+        n = int(round(frac * (T - nt)))
+        for b in range(B):
+            for h in range(H):
+                f[b, h, nt + rng.permutation(T - nt)[:n]] = 1
+        return f
+    M = None if name == "fc80" else video_sweep_mask(rng, B, H, T, nt, 0.2, False)
+    flags = None if name == "bss80" else vision_flags(0.8 if name == "fc80" else 0.5)
+    return M, flags
+
+
 def structured_qk(seed, B, H, L, D, block, signal=1.2):
     """Q, K with block-level structure, for the symbol generation of an Update step: every block of `block`
     tokens shares a random direction of strength `signal` on top of N(0,1) noise, so that the mean-pooled

@@ -29,7 +29,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = pkg.load_library()
     names = _declared_functions()
-    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and "sparse_gemm_o" in names and "sparse_symbols_update" in names and "sparse_op_reuse" in names and "sparse_taylor_coefficients" in names and "sparse_attn_probe_mfma" in names and "sparse_taylor_update" in names and len(names) >= 19
+    assert "sparse_attn_fwd" in names and "sparse_attn_fwd_stream" in names and "sparse_gemm_q" in names and "sparse_gemm_o" in names and "sparse_symbols_update" in names and "sparse_op_reuse" in names and "sparse_taylor_coefficients" in names and "sparse_taylor_update" in names and len(names) >= 19
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
     assert pkg.sparse_attn_version() >= 100
@@ -250,14 +250,6 @@ def test_plan_create_validation_precedes_any_device_work():
     assert lib.sparse_attn_plan_destroy(None) == 0
 
 
-def test_probe_validation():
-    lib = pkg.load_library()
-    tf = ctypes.c_double(0)
-    assert lib.sparse_attn_probe_mfma(0, 0, ctypes.byref(tf), None) == -1
-    assert lib.sparse_attn_probe_mfma(0, 65, ctypes.byref(tf), None) == -1
-    assert lib.sparse_attn_probe_mfma(1, 3, None, None) == -1
-
-
 def _taylor_update(n_terms=2, n_valid=1, interval=5.0, fresh=FAKE, terms=(0x20000000, 0x30000000), n=1024, null_terms=False):
     t = None if null_terms else _ptr_array(list(terms))
     return pkg.load_library().sparse_taylor_update(fresh, t, n_terms, n_valid, interval, n, None)
@@ -274,3 +266,51 @@ def _taylor_update(n_terms=2, n_valid=1, interval=5.0, fresh=FAKE, terms=(0x2000
 def test_taylor_update_argument_validation_precedes_any_device_work(kw, code):
     assert _taylor_update(**kw) == code
     assert pkg.sparse_attn_last_error() != ""
+
+
+def _cpu_case(B=1, H=2, L=256, D=64, bq=64, bk=128):
+    import torch
+    Tq, Tkv = -(-L // bq), -(-L // bk)
+    t = lambda: torch.zeros((B, H, L, D), dtype=torch.bfloat16)
+    return dict(Q=t(), K=t(), V=t(), O=t(), O_cache=t(), flags=torch.zeros((B, H, Tq), dtype=torch.uint8),
+                mask=torch.zeros((B, H, Tq, (Tkv + 7) // 8), dtype=torch.uint8), bq=bq, bk=bk)
+
+
+@pytest.mark.parametrize("field,make,needle", [
+    ("Q", lambda t: t.float(), "dtype"),
+    ("V", lambda t: t.to(__import__("torch").float16), "dtype"),
+    ("K", lambda t: t[:, :, :128], "shape"),
+    ("O", lambda t: t[:, :1], "shape"),
+    ("O_cache", lambda t: t[..., :32], "shape"),
+    ("flags", lambda t: t.to(__import__("torch").int32), "dtype"),
+    ("flags", lambda t: t.bool(), "dtype"),
+    ("flags", lambda t: t[..., :3], "shape"),                  # Tq = 4
+    ("mask", lambda t: t.to(__import__("torch").int64), "dtype"),
+    ("mask", lambda t: __import__("torch").zeros((1, 2, 4, 2), dtype=__import__("torch").uint8), "shape"),   # packed for block_k = 64
+    ("mask", lambda t: t[:, :, :2], "shape"),
+])
+def test_binding_rejects_tensors_the_kernels_would_read_past(field, make, needle):
+    """Wrong dtype or shape is caught in the binding, before any pointer reaches the library (CPU tensors suffice:
+    the checks come first, and a tensor that passes them but is not in device memory is rejected after them)."""
+    c = _cpu_case()
+    c[field] = make(c[field])
+    with pytest.raises(ValueError, match=needle):
+        pkg.sparse_attn_fwd(c["Q"], c["K"], c["V"], c["flags"], c["mask"], c["O_cache"], c["O"], c["bq"], c["bk"])
+    with pytest.raises(ValueError, match=needle):
+        pkg.sparse_attn_fwd_noalloc(c["Q"], c["K"], c["V"], c["flags"], c["mask"], c["O_cache"], c["O"], c["bq"], c["bk"])
+    ok = _cpu_case()
+    with pytest.raises(ValueError, match="device memory"):
+        pkg.sparse_attn_fwd(ok["Q"], ok["K"], ok["V"], ok["flags"], ok["mask"], ok["O_cache"], ok["O"], ok["bq"], ok["bk"])
+
+
+def test_plan_binding_checks_symbol_shapes_with_granularity():
+    import torch
+    B, H, L, bq, bk, n = 1, 2, 1280, 128, 64, 3          # Tq = 10, Tkv = 20 -> 4 x 7 symbols, 1 mask byte per row
+    good_f = torch.zeros((B, H, 4), dtype=torch.uint8)
+    good_m = torch.zeros((B, H, 4, 1), dtype=torch.uint8)
+    for f, m, needle in ((good_f[..., :3], good_m, "shape"), (good_f, torch.zeros((B, H, 4, 3), dtype=torch.uint8), "shape"),
+                         (good_f.int(), good_m, "dtype"), (good_f, good_m.bool(), "dtype")):
+        with pytest.raises(ValueError, match=needle):
+            pkg.SparseAttnPlan(f, m, B, H, L, bq, bk, granularity=n)
+    with pytest.raises(ValueError, match="device memory"):
+        pkg.SparseAttnPlan(good_f, good_m, B, H, L, bq, bk, granularity=n)

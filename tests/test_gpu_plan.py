@@ -90,7 +90,6 @@ def test_granularity_decodes_like_the_expanded_symbols(n, L):
 
 
 def test_plan_without_symbols_is_dense_attention_and_skips_the_prepass_time():
-    w = synth.config_image_skip() if hasattr(synth, "config_image_skip") else None
     w = synth.random_case(synth.BASE_SEED + 99, 1, 4, 4608, 128, 128, 128, keep=1.0)
     case = DeviceCase(w)
     plan = pkg.SparseAttnPlan(None, None, w.B, w.H, w.L, 128, 128)
@@ -117,9 +116,3 @@ def test_plan_without_symbols_is_dense_attention_and_skips_the_prepass_time():
     t_shot = timed(lambda: pkg.sparse_attn_fwd(case.Q, case.K, case.V, None, None, None, O1, 128, 128))
     print(f"[plan] 4608 tokens x 4 heads dense: stored plan {t_plan * 1e3:.1f} us/call, one-shot {t_shot * 1e3:.1f} us/call", flush=True)
     plan.destroy()
-
-
-def test_mfma_probe_reports_a_plausible_rate():
-    tf, mhz = pkg.sparse_attn_probe_mfma(True, launches=2)
-    print(f"[probe] MFMA-only loop, random operands: {tf:.0f} TFLOP/s at {mhz:.0f} MHz", flush=True)
-    assert 300.0 < tf < 2600.0 and 500.0 < mhz < 2600.0

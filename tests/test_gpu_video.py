@@ -67,13 +67,33 @@ def video_tensors():
     return w
 
 
-@pytest.mark.parametrize("keep,skewed,nblocks", [(0.25, False, 64), (0.25, True, 64), (0.0625, False, 64), (1.0, False, 6)])
+@pytest.mark.parametrize("keep,skewed,nblocks", [(0.25, False, 64), (0.25, True, 64), (0.0625, False, 64), (1.0, False, 6),
+                                                 (0.5, False, 32), (0.125, False, 64), (0.5, True, 32), (0.125, True, 64)])
 def test_config5_video_sweep_full_size(video_tensors, keep, skewed, nblocks):
     print(f"[case] config 5 video sweep keep={keep} skewed={skewed}", flush=True)
     base = video_tensors
     w = synth.config_video_sweep(keep, skewed, tensors=(base.Q, base.K, base.V))
     got = DeviceCase(w).run()
     _compare_sample(w, got, _sample_items(w, nblocks, 5), f"config5 keep={keep} skewed={skewed}")
+
+
+@pytest.mark.parametrize("name", synth.PAPER_POINTS)
+def test_paper_operating_points_full_size(video_tensors, name):
+    """The three points the benchmark quotes next to the paper's figures (80 % skipping, 80 % caching, 90 %
+    combined), with the symbols the benchmark times: every cached block bit for bit, 64 computed blocks against
+    the oracle."""
+    print(f"[case] paper operating point {name}", flush=True)
+    base = video_tensors
+    M, flags = synth.paper_operating_point(name)
+    rng = np.random.default_rng(synth.BASE_SEED + 66)
+    Oc = None if flags is None else synth.normal_bf16(rng, base.Q.shape)
+    w = synth.Workload(name, base.B, base.H, base.L, base.D, base.block_q, base.block_k, base.Q, base.K, base.V,
+                       np.ones((base.B, base.H, base.Tq, base.Tkv), dtype=np.uint8) if M is None else M, flags, Oc, {})
+    got = DeviceCase(w).run()
+    if flags is not None:
+        c = np.repeat(flags != 0, w.block_q, axis=2)
+        assert c.any() and (got[c] == Oc[c]).all(), "cached blocks are not bit exact"
+    _compare_sample(w, got, _sample_items(w, 64 if M is not None else 8, 6), name)
 
 
 def test_zero_query_closed_form_at_video_size():
