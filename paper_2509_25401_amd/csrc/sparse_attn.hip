@@ -152,10 +152,13 @@ __global__ void reset_queues(const uint32_t* __restrict__ init, uint32_t* __rest
 // an XCD stream the K/V of one head at a time through that XCD's L2); inside a queue the
 // heaviest rows first (kBuckets kept-count buckets, longest-processing-time-first), rows of one
 // head adjacent inside a bucket, cached rows (plain copies) last.
+__device__ inline int order_major(int key, int Tkv) {
+  // kept count < 2^16 and kBuckets = 16: the product fits in 32 bits
+  return key < 0 ? kBuckets : (kBuckets - 1) - (int)((unsigned)(key & 0xffff) * kBuckets / (unsigned)(Tkv + 1));
+}
 __device__ inline int order_bin(int key, int row, int Tq, int Tkv, int shift, int groups) {
   const int bh = row / Tq;
-  const int major = key < 0 ? kBuckets : (kBuckets - 1) - (int)(((long long)(key & 0xffff) * kBuckets) / (Tkv + 1));
-  return ((bh % kXcds) * (kBuckets + 1) + major) * groups + ((bh / kXcds) >> shift);
+  return ((bh % kXcds) * (kBuckets + 1) + order_major(key, Tkv)) * groups + ((bh / kXcds) >> shift);
 }
 
 __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __restrict__ keys, int N, int Tq,
@@ -198,6 +201,42 @@ __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __res
     if (tid == kXcds - 1) queues[kEndOffset + kXcds - 1] = (uint32_t)N;
   }
   __syncthreads();
+  // Inside a bin the rows keep their order in the sequence: neighbouring query blocks, which with windowed symbols
+  // keep nearly the same key blocks, are then worked on at the same time and find each other's tiles in L2.  A bin
+  // holds rows of one head as long as there are no more than kMaxHeadGroups heads per queue: a wave then walks a
+  // head 64 query blocks at a time, lane b counts the rows seen so far in bucket b, and a row's place is the start
+  // of its bin + that count + the rows of its bucket at lower lanes (ballots).  With more heads several of them
+  // share a bin and the rows take their places in arrival order.
+  if (shift == 0) {
+    const int wave = tid >> 6, lane = tid & 63;
+    const int heads = N / Tq;
+    for (int bh = wave; bh < heads; bh += kOrderThreads / 64) {
+      uint32_t seen = 0;                                   // lane b: rows of this head in bucket b so far
+      for (int i0 = 0; i0 < Tq; i0 += 64) {
+        const int i = i0 + lane;
+        const bool valid = i < Tq;
+        const int r = bh * Tq + min(i, Tq - 1);
+        const int key = keys[r];
+        const int major = valid ? order_major(key, Tkv) : -1;
+        unsigned long long todo = __ballot(valid);
+        uint32_t rank = 0;
+        while (todo != 0ull) {
+          const int cur = __shfl(major, (int)__builtin_ctzll(todo));
+          const unsigned long long same = __ballot(major == cur);
+          const uint32_t before = __shfl(seen, cur);
+          if (major == cur) rank = before + (uint32_t)__popcll(same & ((1ull << lane) - 1ull));
+          if (lane == cur) seen += (uint32_t)__popcll(same);
+          todo &= ~same;
+        }
+        if (valid) {
+          const uint32_t pos = bins[order_bin(key, r, Tq, Tkv, shift, groups)] + rank;
+          order[2 * pos] = (uint32_t)r | (key < 0 ? kCopyFlag : 0u);
+          order[2 * pos + 1] = (uint32_t)key;
+        }
+      }
+    }
+    return;
+  }
   for (int r = tid; r < N; r += kOrderThreads) {
     const int key = keys[r];
     const uint32_t pos = atomicAdd(&bins[order_bin(key, r, Tq, Tkv, shift, groups)], 1u);
