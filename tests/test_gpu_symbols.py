@@ -11,12 +11,9 @@ import oracle
 import paper_2509_25401_amd as pkg
 from paper_2509_25401_amd import synth
 from gpu_utils import dev, up_bf16, down_bits, check_against_oracle
+from helpers import compare_symbols
 
 pytestmark = pytest.mark.gpu
-
-EPS_FLAG = 1e-4     # relative to the metric's total
-EPS_SKIP = 2e-5     # absolute: rows of the map sum to one
-
 
 def f32(x):
     return float(np.float32(x))
@@ -24,7 +21,7 @@ def f32(x):
 
 def run_gpu(Q, K, block, text, tau_c, tau_kv, s_q=0.0):
     B, H, L, D = Q.shape
-    T = L // block
+    T = -(-L // block)
     flags = torch.full((B, H, T), 0xAA, dtype=torch.uint8, device=dev())
     mask = torch.full((B, H, T, (T + 7) // 8), 0xAA, dtype=torch.uint8, device=dev())
     pkg.sparse_symbols_update(up_bf16(Q), up_bf16(K), flags, mask, block, text, tau_c, tau_kv, s_q)
@@ -32,22 +29,14 @@ def run_gpu(Q, K, block, text, tau_c, tau_kv, s_q=0.0):
     return flags.cpu().numpy(), mask.cpu().numpy()
 
 
-def compare(ref, flags, mask, T, label, max_ambiguous=0.02):
+def compare(ref, flags, mask, T, label, max_ambiguous=0.02, require_identical=True):
+    """On the structured test inputs the fp32 kernels reproduce every decision of the fp64 oracle, so the raw
+    symbols are required to be identical; the margin rule of helpers.compare_symbols stays in force underneath
+    (it is what the statement "a decision within rounding of its threshold may differ" means)."""
     bits = oracle.unpack_symbols(mask, T)
-    # padding bits of the last byte are zero
-    if T % 8:
+    if T % 8:    # padding bits of the last byte are zero
         assert (mask[..., -1] & ((1 << (8 - T % 8)) - 1) == 0).all(), f"{label}: padding bits set"
-    assert set(np.unique(flags)) <= {0, 1}
-    robust_f = ref["flag_margin"] > EPS_FLAG + np.where(ref["flag_tie"], 2 * ref["flag_window"], 0.0)
-    robust_s = np.abs(ref["skip_margin"]) > EPS_SKIP + np.where(ref["skip_tie"], 2 * ref["own_value"], 0.0)
-    bad_f = (flags != ref["cache_flags"]) & robust_f
-    bad_s = (bits != ref["M_s"]) & robust_s
-    print(f"[symbols] {label}: cached {ref['cache_flags'].mean():.3f} kept {ref['M_s'].mean():.3f} "
-          f"undecidable flags {(~robust_f).mean():.4f} pairs {(~robust_s).mean():.5f} "
-          f"raw mismatches flags {(flags != ref['cache_flags']).sum()} pairs {(bits != ref['M_s']).sum()}", flush=True)
-    assert not bad_f.any(), f"{label}: {bad_f.sum()} cache flags differ from the oracle beyond rounding"
-    assert not bad_s.any(), f"{label}: {bad_s.sum()} mask bits differ from the oracle beyond rounding"
-    assert (~robust_f).mean() <= max_ambiguous and (~robust_s).mean() <= max_ambiguous
+    compare_symbols(ref, flags, bits, label, max_ambiguous, require_identical)
     return bits
 
 
@@ -146,15 +135,5 @@ def test_short_last_block(L, D, block, text):
     Q, K = np.ascontiguousarray(Q[:, :, :L]), np.ascontiguousarray(K[:, :, :L])
     tau_c, tau_kv = f32(0.5), f32(0.2)
     ref = oracle.update_symbols(Q, K, block, text, tau_c, tau_kv)
-    flags, mask = run_gpu_ragged(Q, K, block, text, tau_c, tau_kv)
+    flags, mask = run_gpu(Q, K, block, text, tau_c, tau_kv)
     compare(ref, flags, mask, T, f"ragged L{L}_D{D}_b{block}", max_ambiguous=0.05)
-
-
-def run_gpu_ragged(Q, K, block, text, tau_c, tau_kv):
-    B, H, L, D = Q.shape
-    T = -(-L // block)
-    flags = torch.full((B, H, T), 0xAA, dtype=torch.uint8, device=dev())
-    mask = torch.full((B, H, T, (T + 7) // 8), 0xAA, dtype=torch.uint8, device=dev())
-    pkg.sparse_symbols_update(up_bf16(Q), up_bf16(K), flags, mask, block, text, tau_c, tau_kv)
-    torch.cuda.synchronize()
-    return flags.cpu().numpy(), mask.cpu().numpy()
