@@ -263,25 +263,31 @@ int sparse_taylor_update(const void* fresh, void* const* terms, int n_terms, int
 /*
  * Sparse-symbol generation of an Update step (Section 3.3 "Logical Masks Generation", Equation 1; the
  * tau_kv and S_q rules of the settings table in the appendix).  From the step's Q and K it writes the
- * two symbol arrays that sparse_attn_fwd, sparse_gemm_q and sparse_gemm_o read at the following steps.
- * Per (batch, head), with T = ceil(L / block) blocks (a short last block is pooled over the tokens that exist)
- * of which the first text_tokens / block are text:
- *   1. q~, k~ = per-block means of the query / key rows; P~ = row softmax of q~ k~^T / sqrt(D)
- *   2. C_v = sum over text rows of P~[row, vision block v]; G_v = sum over text columns j of
- *      softmax over v of P~[vision block v, j]
- *   3. vision block v is cached iff the ascending cumulative sums (ties by index) of C and of G at v are
+ * two symbol arrays that the attention calls, sparse_gemm_q and sparse_gemm_o read at the following steps.
+ * Per (batch, head), with symbol granularity n: pooled query blocks of n * block_q tokens, T_q = ceil(L / (n block_q))
+ * of them, and pooled key blocks of n * block_k tokens, T_k = ceil(L / (n block_k)) (a short last block is pooled
+ * over the tokens that exist); the first ceil(text_tokens / (n block_q)) query blocks and ceil(text_tokens /
+ * (n block_k)) key blocks are text (a pooled block that holds any text token is a text block):
+ *   1. q~, k~ = per-block means of the query / key rows; P~ = row softmax of q~ k~^T / sqrt(D), [T_q, T_k]
+ *   2. C_u = sum over text rows of P~[row, vision key block u], carried over to the vision query blocks by token
+ *      overlap when n block_q != n block_k (C_v = sum_u C_u * |v and u| / |u|); G_v = sum over text columns j of
+ *      softmax over v of P~[vision query block v, j]
+ *   3. vision query block v is cached iff the ascending cumulative sums (ties by index) of C and of G at v are
  *      both <= tau_c times the totals; text blocks are never cached; if afterwards the share of the
- *      head's blocks that still need computation is below s_q, all T blocks are cached
+ *      head's blocks that still need computation is below s_q, all T_q blocks are cached
  *   4. in row i of P~ key block j is skipped iff the ascending cumulative sum at j is <= tau_kv
  * All arithmetic is fp32; a decision whose deciding sum lies within rounding of its threshold may
  * differ from an exact evaluation.
  *   Q, K         device, bf16 [B, H, L, D], 16-byte aligned (read once each)
- *   cache_flags  device, uint8 [B, H, T], written: 1 = cached
- *   kv_mask      device, uint8 [B, H, T, ceil(T/8)], written: bit = 1 keeps the pair, first block in
+ *   cache_flags  device, uint8 [B, H, T_q], written: 1 = cached
+ *   kv_mask      device, uint8 [B, H, T_q, ceil(T_k / 8)], written: bit = 1 keeps the pair, first block in
  *                bit 7 of byte 0, padding bits 0
- *   text_tokens  number of leading text tokens, a positive multiple of block, < L
+ *   text_tokens  number of leading text tokens, 0 < text_tokens < L, with at least one vision block left on both axes
  *   tau_c, tau_kv, s_q  in [0, 1]
- * Supported: D and block in {64, 128}, T <= 2048.  block is both b_q and b_k (granularity n = 1).
+ * The arrays are exactly what sparse_attn_plan_create(..., block_q, block_k, granularity) reads; with granularity 1
+ * they are what sparse_attn_fwd reads.  sparse_symbols_update / _stream are the case block_q = block_k = block,
+ * granularity 1.
+ * Supported: D, block_q, block_k in {64, 128}, granularity 1..64, T_q and T_k <= 2048.
  * Uses the library's per-stream scratch buffer (grown with hipMalloc on first use).  Errors as for
  * sparse_attn_fwd.
  */
@@ -290,6 +296,9 @@ int sparse_symbols_update(const void* Q, const void* K, uint8_t* cache_flags, ui
 int sparse_symbols_update_stream(const void* Q, const void* K, uint8_t* cache_flags, uint8_t* kv_mask, int B, int H,
                                  int L, int D, int block, int text_tokens, float tau_c, float tau_kv, float s_q,
                                  void* hip_stream);
+int sparse_symbols_update_granular(const void* Q, const void* K, uint8_t* cache_flags, uint8_t* kv_mask, int B, int H,
+                                   int L, int D, int block_q, int block_k, int granularity, int text_tokens,
+                                   float tau_c, float tau_kv, float s_q, void* hip_stream);
 
 /*
  * Live kernel timing for benchmarks.  Between sparse_attn_profile_begin(max_calls) and

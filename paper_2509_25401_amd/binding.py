@@ -81,6 +81,8 @@ def load_library():
     lib.sparse_symbols_update.restype = i32
     lib.sparse_symbols_update_stream.argtypes = [vp] * 4 + [i32] * 6 + [f32] * 3 + [vp]
     lib.sparse_symbols_update_stream.restype = i32
+    lib.sparse_symbols_update_granular.argtypes = [vp] * 4 + [i32] * 8 + [f32] * 3 + [vp]
+    lib.sparse_symbols_update_granular.restype = i32
     lib.sparse_attn_profile_begin.argtypes = [i32]
     lib.sparse_attn_profile_begin.restype = i32
     lib.sparse_attn_profile_end.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -386,19 +388,29 @@ def sparse_taylor_coefficients(order, steps):
     return [float(x) for x in buf]
 
 
-def sparse_symbols_update(Q, K, cache_flags, kv_mask, block, text_tokens, tau_c, tau_kv, s_q=0.0, stream=None):
-    """Symbol generation of an Update step on device tensors: Q, K bf16 [B,H,L,D]; writes cache_flags uint8 [B,H,T]
-    (1 = cached) and kv_mask uint8 [B,H,T,ceil(T/8)] (bit = 1 keeps the pair, first block in bit 7), T = L/block."""
-    B, H, L, D = Q.shape
-    if tuple(K.shape) != (B, H, L, D):
-        raise ValueError("Q and K must have the same shape [B,H,L,D]")
-    T = -(-L // block)
-    if tuple(cache_flags.shape) != (B, H, T) or tuple(kv_mask.shape) != (B, H, T, (T + 7) // 8):
-        raise ValueError("cache_flags must be [B,H,T] and kv_mask [B,H,T,ceil(T/8)] with T = ceil(L/block)")
-    rc = load_library().sparse_symbols_update_stream(_dev_ptr(Q, "Q"), _dev_ptr(K, "K"),
-                                                     _dev_ptr(cache_flags, "cache_flags"), _dev_ptr(kv_mask, "kv_mask"),
-                                                     int(B), int(H), int(L), int(D), int(block), int(text_tokens),
-                                                     float(tau_c), float(tau_kv), float(s_q), _stream_ptr(stream))
+def sparse_symbols_update(Q, K, cache_flags, kv_mask, block, text_tokens, tau_c, tau_kv, s_q=0.0, stream=None,
+                          block_k=None, granularity=1):
+    """Symbol generation of an Update step on device tensors: Q, K bf16 [B,H,L,D]; writes cache_flags uint8 [B,H,Tq]
+    (1 = cached) and kv_mask uint8 [B,H,Tq,ceil(Tk/8)] (bit = 1 keeps the pair, first block in bit 7), with
+    Tq = ceil(L / (granularity * block)), Tk = ceil(L / (granularity * block_k)); block is b_q, block_k defaults to it."""
+    import torch
+    block_k = block if block_k is None else block_k
+    if Q.dim() != 4:
+        raise ValueError("Q must be [B, H, L, D]")
+    B, H, L, D = (int(x) for x in Q.shape)
+    if int(block) <= 0 or int(block_k) <= 0 or int(granularity) <= 0:
+        raise ValueError("block sizes and granularity must be positive")
+    Tq, Tk = _ceil_div(L, granularity * block), _ceil_div(L, granularity * block_k)
+    _check(Q, "Q", torch.bfloat16, (B, H, L, D))
+    _check(K, "K", torch.bfloat16, (B, H, L, D))
+    _check(cache_flags, "cache_flags", torch.uint8, (B, H, Tq))
+    _check(kv_mask, "kv_mask", torch.uint8, (B, H, Tq, _ceil_div(Tk, 8)))
+    _same_device((Q, K, cache_flags, kv_mask))
+    rc = load_library().sparse_symbols_update_granular(_dev_ptr(Q, "Q"), _dev_ptr(K, "K"),
+                                                       _dev_ptr(cache_flags, "cache_flags"), _dev_ptr(kv_mask, "kv_mask"),
+                                                       B, H, L, D, int(block), int(block_k), int(granularity),
+                                                       int(text_tokens), float(tau_c), float(tau_kv), float(s_q),
+                                                       _stream_ptr(stream))
     if rc != 0:
         _raise(rc)
     return cache_flags, kv_mask

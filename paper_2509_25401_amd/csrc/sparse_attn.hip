@@ -9,8 +9,8 @@
 //               of one head adjacent inside a bucket, cached rows (plain copies) last;
 //   attn        a persistent grid of two workgroups per CU pulls items from its XCD's queue and
 //               steals from the others when that is drained.  A compute item is one query block:
-//               Q lives in registers (pre-multiplied by log2(e)/sqrt(D)), the reduction-axis
-//               symbol is walked with scalar find-first-set on the decoded words, and only kept
+//               Q lives in registers as stored (the 1/sqrt(D) scale is applied to the fp32 score),
+//               the reduction-axis symbol is walked with scalar find-first-set on the decoded words, and only kept
 //               K/V tiles are streamed to LDS with direct-to-LDS loads, double buffered in 64-key
 //               sub-tiles.  S^T = K Q^T and O^T = V^T P^T run on v_mfma_f32_32x32x16_bf16, so
 //               each lane owns one query row: the row maximum needs a single half-wave exchange,
@@ -326,7 +326,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
   const int half = lane >> 5;   // which 8 of the 16 k-slots of an MFMA this lane feeds
   const int i16 = lane & 15;
   const int g4 = lane >> 4;
-  const float c = p.scale_log2;
+  const float score_scale = p.scale_log2;
 
   // Per-lane offsets, the same for every item.
   // Global byte offsets inside a sub-tile (swizzle applied to the source).  The swizzles repeat every 16 rows, so
@@ -441,9 +441,9 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     const char* Vh = p.V + head_off;
     const uint32_t* wp = p.words + (size_t)row * p.nw32;
 
-    // Q fragment: B operand of S^T = K Q^T; lane holds query row l32, d = 16*ks + 8*half .. +7.
-    // It is multiplied by log2(e)/sqrt(D) once here (rounded back to bf16), so the MFMA result is
-    // already the exponent of 2 and the softmax needs no multiply per score.
+    // Q fragment: B operand of S^T = K Q^T; lane holds query row l32, d = 16*ks + 8*half .. +7, exactly as stored:
+    // the products accumulate in fp32 and the scale log2(e)/sqrt(D) is applied to the fp32 score on its way into
+    // the exponential (scaling the fragment instead would save that multiply but round the queries a second time).
     // (It is loaded further down, behind the first K/V sub-tile's loads, so that the two latencies overlap.)
     bf16x8 qf[KS];
 
@@ -452,7 +452,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
-    // Reference of the exponent (log2 domain) of this lane's query row, kept NEGATED in all 16
+    // Reference of the scores (raw q.k units, before the scale) of this lane's query row, kept NEGATED in all 16
     // registers of an accumulator: it is the C operand of the first MFMA of every S^T block, so
     // the MFMA delivers score - reference and the softmax needs no subtraction per score either.
     // The reference is not the running maximum: it is raised (to the row maximum seen so far) only
@@ -554,8 +554,8 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       auto chunk = [&](int kb2, int c, float& dl) {
         const int g = 2 * kb2 + c / 4, e = 2 * (c % 4);
         bf16x2 pr;
-        pr[0] = (__bf16)__builtin_amdgcn_exp2f(s[kb2][8 * (g & 1) + e]);
-        pr[1] = (__bf16)__builtin_amdgcn_exp2f(s[kb2][8 * (g & 1) + e + 1]);
+        pr[0] = (__bf16)__builtin_amdgcn_exp2f(s[kb2][8 * (g & 1) + e] * score_scale);
+        pr[1] = (__bf16)__builtin_amdgcn_exp2f(s[kb2][8 * (g & 1) + e + 1] * score_scale);
         pb[g][e] = pr[0];
         pb[g][e + 1] = pr[1];
         dl = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, dl, false);
@@ -586,7 +586,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
           for (int e = 0; e < 16; ++e) s[1][e] -= d;
         }
         if (!first) {
-          const float alpha = __builtin_amdgcn_exp2f(-d);
+          const float alpha = __builtin_amdgcn_exp2f(-d * score_scale);
           l_run *= alpha;
 #pragma unroll
           for (int db = 0; db < DB; ++db)
@@ -684,7 +684,7 @@ __global__ void __launch_bounds__(BQ * 2, 2) attn_kernel(const AttnParams p) {
       for (int ks = 0; ks < KS; ++ks) {
         const bf16x8 q = *(const bf16x8*)(qrow + ks * 32);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) qf[ks][e] = (__bf16)((float)q[e] * c);
+        for (int e = 0; e < 8; ++e) qf[ks][e] = q[e];
       }
     }
     // the walk continues behind the first kept block

@@ -2,16 +2,17 @@
 // the tau_kv / S_q rules of the settings table in the appendix) for gfx950.
 //
 // Three kernels, all plain fp32 vector arithmetic:
-//   pool_blocks   mean of the b query rows / key rows of every block: the only pass over Q and K,
-//                 HBM-bound (reads both tensors once, 16 bytes per lane, row-contiguous)
+//   pool_blocks   mean of the n*b_q query rows / n*b_k key rows of every pooled block (granularity n): the only
+//                 pass over Q and K, HBM-bound (reads both tensors once, 16 bytes per lane, row-contiguous)
 //   map_rows      one workgroup per 8 rows of the compressed attention map of one head: scores of the
 //                 pooled queries against all pooled keys (scale 1/sqrt(d)), row softmax, then for
 //                 every row the block-skipping rule -- a key block is skipped iff the sum of all row
 //                 entries that come at or before it in ascending order (ties by index) stays <= tau_kv
 //                 -- packed most-significant-bit first into the kv_mask row.  The text rows and text
 //                 columns of the map (all that the caching rule needs) go to scratch memory.
-//   select_blocks one workgroup per head: contribution C_v = sum over text rows of their weight on
-//                 vision block v, guidance G_v = sum over text columns of the softmax, along the vision
+//   select_blocks one workgroup per head: contribution C_u = sum over text rows of their weight on
+//                 vision key block u (carried over to the vision query blocks by token overlap when
+//                 n*b_q != n*b_k), guidance G_v = sum over text columns of the softmax, along the vision
 //                 axis, of the vision rows' weights on that column; Equation 1 caches v iff its
 //                 ascending cumulative sums of C and of G both stay <= tau_c times the totals; text
 //                 blocks are never cached; if the share of blocks left to compute drops below S_q,
@@ -23,6 +24,7 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "sparse_attn.h"
@@ -83,18 +85,22 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// pooled[which][block][d] = mean over the block's rows; grid (n_blocks, 2), which = 0 for Q, 1 for K
+// Pooled queries [BH][Tq][D], then pooled keys [BH][Tk][D]: mean over the pooled block's rows.  Grid
+// (BH * max(Tq, Tk), 2), y = 0 for Q (pool_q rows per block), 1 for K (pool_k rows per block).
 template <int D>
 __global__ void __launch_bounds__(256) pool_blocks(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
-                                                   float* __restrict__ pooled, int block, int T, int L,
-                                                   long long n_blocks) {
+                                                   float* __restrict__ pooled, int pool_q, int pool_k, int Tq, int Tk,
+                                                   int L, long long n_q_blocks) {
   constexpr int TPR = D / 8;          // threads per row, 8 bf16 = 16 bytes each
   constexpr int RPP = 256 / TPR;      // rows per pass
   __shared__ float part[RPP][D];
-  // block t of head bh; the last block of a head may be short: the mean is over the rows that exist
-  const int bh = blockIdx.x / T, t = blockIdx.x - bh * T;
-  const int rows = min(block, L - t * block);
-  const uint16_t* src = (blockIdx.y ? K : Q) + ((size_t)bh * L + (size_t)t * block) * D;
+  const int Tmax = max(Tq, Tk);
+  const int T = blockIdx.y ? Tk : Tq, pool = blockIdx.y ? pool_k : pool_q;
+  // pooled block t of head bh; the last block of a head may be short: the mean is over the rows that exist
+  const int bh = blockIdx.x / Tmax, t = blockIdx.x - bh * Tmax;
+  if (t >= T) return;
+  const int rows = min(pool, L - t * pool);
+  const uint16_t* src = (blockIdx.y ? K : Q) + ((size_t)bh * L + (size_t)t * pool) * D;
   const int c = threadIdx.x % TPR, r0 = threadIdx.x / TPR;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int r = r0; r < rows; r += RPP) {
@@ -112,7 +118,8 @@ __global__ void __launch_bounds__(256) pool_blocks(const uint16_t* __restrict__ 
   if (threadIdx.x < D) {
     float s = 0.f;
     for (int r = 0; r < RPP; ++r) s += part[r][threadIdx.x];
-    pooled[((size_t)blockIdx.y * n_blocks + blockIdx.x) * D + threadIdx.x] = s / (float)rows;
+    const size_t slot = (blockIdx.y ? (size_t)n_q_blocks : 0) + (size_t)bh * T + t;
+    pooled[slot * D + threadIdx.x] = s / (float)rows;
   }
 }
 
@@ -178,8 +185,8 @@ __device__ __forceinline__ void next_value_ties(const float* pr, int T, int lane
 // Dynamic LDS: pooled query rows [kMapRows][D], one stage of pooled key rows [kChunk][D + 4] (padded so
 // that 16 lanes reading 16 bytes of 16 different rows hit 64 different banks), map rows [kMapRows][T_pad].
 template <int D>
-__global__ void __launch_bounds__(256) map_rows(const float* __restrict__ pooled, long long n_blocks, int T, int T_pad,
-                                                int n_t, int row_bytes, float scale, float tau_kv,
+__global__ void __launch_bounds__(256) map_rows(const float* __restrict__ pooled, long long n_q_blocks, int Tq, int T, int T_pad,
+                                                int n_tq, int n_t, int row_bytes, float scale, float tau_kv,
                                                 uint8_t* __restrict__ kv_mask, float* __restrict__ text_rows,
                                                 float* __restrict__ text_cols) {
   extern __shared__ float lds[];
@@ -188,12 +195,13 @@ __global__ void __launch_bounds__(256) map_rows(const float* __restrict__ pooled
   float* kst = q + kMapRows * D;
   float* p = kst + kChunk * KS;
   const int tid = threadIdx.x;
-  const int groups = (T + kMapRows - 1) / kMapRows;
+  // T = pooled key blocks (columns of the map), n_t of them text; Tq = pooled query blocks (rows), n_tq of them text
+  const int groups = (Tq + kMapRows - 1) / kMapRows;
   const int bh = blockIdx.x / groups, i0 = (blockIdx.x % groups) * kMapRows;
-  const float* qt = pooled + (size_t)bh * T * D;
-  const float* kt = pooled + ((size_t)n_blocks + (size_t)bh * T) * D;
+  const float* qt = pooled + (size_t)bh * Tq * D;
+  const float* kt = pooled + ((size_t)n_q_blocks + (size_t)bh * T) * D;
   for (int e = tid; e < kMapRows * D; e += 256) {
-    const int r = e / D, i = min(i0 + r, T - 1);
+    const int r = e / D, i = min(i0 + r, Tq - 1);
     q[e] = qt[(size_t)i * D + e % D];
   }
   for (int e = tid; e < kMapRows * (T_pad - T); e += 256) p[(e / (T_pad - T)) * T_pad + T + e % (T_pad - T)] = INFINITY;
@@ -256,8 +264,8 @@ __global__ void __launch_bounds__(256) map_rows(const float* __restrict__ pooled
     for (int j = lane; j < T; j += 64) {
       const float v = pr[j] / sum;
       pr[j] = v;
-      if (i < n_t) text_rows[((size_t)bh * n_t + i) * T + j] = v;        // i < n_t < T
-      if (j < n_t && i < T) text_cols[((size_t)bh * T + i) * n_t + j] = v;
+      if (i < n_tq) text_rows[((size_t)bh * n_tq + i) * T + j] = v;       // i < n_tq < Tq
+      if (j < n_t && i < Tq) text_cols[((size_t)bh * Tq + i) * n_t + j] = v;
     }
   }
   __syncthreads();
@@ -285,36 +293,57 @@ __global__ void __launch_bounds__(256) map_rows(const float* __restrict__ pooled
     // lanes 0-7 write the bytes of row a, lanes 8-15 those of row b; first block of a byte = bit 7
     const int byte = j0 / 8 + (lane & 7);
     const int i = lane < 8 ? ia : ib;
-    if (lane < 16 && i < T && byte < row_bytes) {
+    if (lane < 16 && i < Tq && byte < row_bytes) {
       const unsigned long long kept = lane < 8 ? kept_a : kept_b;
       const unsigned bits = (unsigned)(kept >> (8 * (lane & 7))) & 0xffu;
-      kv_mask[((size_t)bh * T + i) * row_bytes + byte] = (uint8_t)(__brev(bits) >> 24);
+      kv_mask[((size_t)bh * Tq + i) * row_bytes + byte] = (uint8_t)(__brev(bits) >> 24);
     }
   }
 }
 
+// Tq / Tk pooled query / key blocks, n_tq / n_tk of them text; pool_q / pool_k tokens per pooled block.
 __global__ void __launch_bounds__(256) select_blocks(const float* __restrict__ text_rows,
-                                                     const float* __restrict__ text_cols, int T, int n_t, float tau_c,
-                                                     float s_q, uint8_t* __restrict__ cache_flags) {
-  __shared__ float C[kMaxBlocks], G[kMaxBlocks];
+                                                     const float* __restrict__ text_cols, int Tq, int Tk, int n_tq,
+                                                     int n_tk, int pool_q, int pool_k, int L, float tau_c, float s_q,
+                                                     uint8_t* __restrict__ cache_flags) {
+  __shared__ float C[kMaxBlocks], G[kMaxBlocks], Ck[kMaxBlocks];
   __shared__ float red[4];
-  const int bh = blockIdx.x, Tv = T - n_t, tid = threadIdx.x;
-  const float* tr = text_rows + (size_t)bh * n_t * T;
-  const float* tc = text_cols + (size_t)bh * T * n_t;
-  for (int v = tid; v < Tv; v += 256) {
+  const int bh = blockIdx.x, Tv = Tq - n_tq, Tu = Tk - n_tk, tid = threadIdx.x;
+  const float* tr = text_rows + (size_t)bh * n_tq * Tk;
+  const float* tc = text_cols + (size_t)bh * Tq * n_tk;
+  // contribution of every vision key block: what the text rows put on it
+  for (int u = tid; u < Tu; u += 256) {
     float c = 0.f;
-    for (int j = 0; j < n_t; ++j) c += tr[(size_t)j * T + n_t + v];
+    for (int j = 0; j < n_tq; ++j) c += tr[(size_t)j * Tk + n_tk + u];
+    Ck[u] = c;
+  }
+  __syncthreads();
+  for (int v = tid; v < Tv; v += 256) {
+    float c;
+    if (pool_q == pool_k) {
+      c = Ck[v];
+    } else {
+      // carried over to the query axis: every key block's contribution spread evenly over its tokens
+      c = 0.f;
+      const int q0 = (n_tq + v) * pool_q, q1 = min(q0 + pool_q, L);
+      const int u_lo = max(q0 / pool_k - n_tk, 0), u_hi = min((q1 - 1) / pool_k - n_tk, Tu - 1);
+      for (int u = u_lo; u <= u_hi; ++u) {
+        const int k0 = (n_tk + u) * pool_k, k1 = min(k0 + pool_k, L);
+        const int common = min(k1, q1) - max(k0, q0);
+        if (common > 0) c += Ck[u] * (float)common / (float)(k1 - k0);
+      }
+    }
     C[v] = c;
     G[v] = 0.f;
   }
-  for (int j = 0; j < n_t; ++j) {
+  for (int j = 0; j < n_tk; ++j) {
     float m = -INFINITY;
-    for (int v = tid; v < Tv; v += 256) m = fmaxf(m, tc[(size_t)(n_t + v) * n_t + j]);
+    for (int v = tid; v < Tv; v += 256) m = fmaxf(m, tc[(size_t)(n_tq + v) * n_tk + j]);
     m = block_max(m, red);
     float s = 0.f;
-    for (int v = tid; v < Tv; v += 256) s += expf(tc[(size_t)(n_t + v) * n_t + j] - m);
+    for (int v = tid; v < Tv; v += 256) s += expf(tc[(size_t)(n_tq + v) * n_tk + j] - m);
     s = block_sum(s, red);
-    for (int v = tid; v < Tv; v += 256) G[v] += expf(tc[(size_t)(n_t + v) * n_t + j] - m) / s;   // v belongs to one thread
+    for (int v = tid; v < Tv; v += 256) G[v] += expf(tc[(size_t)(n_tq + v) * n_tk + j] - m) / s;   // v belongs to one thread
   }
   __syncthreads();
   // totals in index order: what the ascending sum of the largest entry adds up to as well
@@ -338,10 +367,10 @@ __global__ void __launch_bounds__(256) select_blocks(const float* __restrict__ t
     n_cached += cached ? 1 : 0;
   }
   const float total_cached = block_sum((float)n_cached, red);    // exact: counts stay far below 2^24
-  const bool degrade = ((float)T - total_cached) / (float)T < s_q;
-  uint8_t* out = cache_flags + (size_t)bh * T;
-  for (int b = tid; b < n_t; b += 256) out[b] = degrade ? 1 : 0;
-  for (int v = tid, n = 0; v < Tv; v += 256, ++n) out[n_t + v] = (degrade || ((mine >> n) & 1u)) ? 1 : 0;
+  const bool degrade = ((float)Tq - total_cached) / (float)Tq < s_q;
+  uint8_t* out = cache_flags + (size_t)bh * Tq;
+  for (int b = tid; b < n_tq; b += 256) out[b] = degrade ? 1 : 0;
+  for (int v = tid, n = 0; v < Tv; v += 256, ++n) out[n_tq + v] = (degrade || ((mine >> n) & 1u)) ? 1 : 0;
 }
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -356,70 +385,91 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 extern "C" {
 
-int sparse_symbols_update_stream(const void* Q, const void* K, uint8_t* cache_flags, uint8_t* kv_mask, int B, int H,
-                                 int L, int D, int block, int text_tokens, float tau_c, float tau_kv, float s_q,
-                                 void* hip_stream) {
-  if (B <= 0 || H <= 0 || L <= 0 || D <= 0 || block <= 0)
-    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: sizes must be positive (B=%d H=%d L=%d D=%d block=%d)", B, H, L, D,
-                   block);
-  if ((D != 64 && D != 128) || (block != 64 && block != 128))
-    return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: D and block must be 64 or 128 (got %d, %d)", D, block);
-  if (text_tokens % block)
-    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: text_tokens=%d must be a multiple of block=%d", text_tokens, block);
+int sparse_symbols_update_granular(const void* Q, const void* K, uint8_t* cache_flags, uint8_t* kv_mask, int B, int H,
+                                   int L, int D, int block_q, int block_k, int granularity, int text_tokens, float tau_c,
+                                   float tau_kv, float s_q, void* hip_stream) {
+  if (B <= 0 || H <= 0 || L <= 0 || D <= 0 || block_q <= 0 || block_k <= 0)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: sizes must be positive (B=%d H=%d L=%d D=%d block_q=%d block_k=%d)", B, H,
+                   L, D, block_q, block_k);
+  if ((D != 64 && D != 128) || (block_q != 64 && block_q != 128) || (block_k != 64 && block_k != 128))
+    return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: D, block_q and block_k must be 64 or 128 (got %d, %d, %d)", D,
+                   block_q, block_k);
+  if (granularity < 1 || granularity > 64)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: granularity=%d must be between 1 and 64", granularity);
   if (text_tokens <= 0 || text_tokens >= L)
-    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: text_tokens=%d must leave text and vision blocks (L=%d)",
-                   text_tokens, L);
-  const int T = (L + block - 1) / block, n_t = text_tokens / block;   // a short last block counts as a block
-  if (T > kMaxBlocks) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: %d blocks exceed %d", T, kMaxBlocks);
-  if (T - n_t > 256 * 32) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: too many vision blocks (%d)", T - n_t);
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: text_tokens=%d must leave text and vision tokens (L=%d)", text_tokens, L);
+  // pooled blocks of n * b tokens; a short last block counts as a block, and a pooled block that holds any text
+  // token counts as text (the ceiling of Section 3.3)
+  const int pool_q = granularity * block_q, pool_k = granularity * block_k;
+  const int Tq = (L + pool_q - 1) / pool_q, Tk = (L + pool_k - 1) / pool_k;
+  const int n_tq = (text_tokens + pool_q - 1) / pool_q, n_tk = (text_tokens + pool_k - 1) / pool_k;
+  if (n_tq >= Tq || n_tk >= Tk)
+    return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: no vision block is left (%d of %d query blocks and %d of %d key blocks are text)",
+                   n_tq, Tq, n_tk, Tk);
+  if (Tq > kMaxBlocks || Tk > kMaxBlocks)
+    return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: %d x %d pooled blocks exceed %d", Tq, Tk, kMaxBlocks);
   if (!(tau_c >= 0.f && tau_c <= 1.f) || !(tau_kv >= 0.f && tau_kv <= 1.f) || !(s_q >= 0.f && s_q <= 1.f))
     return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: tau_c, tau_kv and s_q must lie in [0, 1] (got %g, %g, %g)",
                    (double)tau_c, (double)tau_kv, (double)s_q);
-  const long long n_blocks = (long long)B * H * T;
-  if (n_blocks > 0x3fffffffLL) return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: too many blocks (%lld)", n_blocks);
+  const long long BH = (long long)B * H;
+  const long long n_q_blocks = BH * Tq, n_k_blocks = BH * Tk;
+  if (BH * (Tq > Tk ? Tq : Tk) > 0x3fffffffLL)
+    return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "symbols: too many blocks (%lld)", BH * (Tq > Tk ? Tq : Tk));
   if (!Q || !K || !cache_flags || !kv_mask)
     return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: Q, K, cache_flags and kv_mask must not be NULL");
   if (((uintptr_t)Q | (uintptr_t)K) & 15) return sa_fail(SPARSE_ATTN_ERR_INVALID, "symbols: Q and K must be 16-byte aligned");
 
   hipStream_t stream = (hipStream_t)hip_stream;
-  const size_t pooled_b = align256((size_t)2 * n_blocks * D * 4);
-  const size_t slice_b = align256((size_t)B * H * n_t * T * 4);
+  const size_t pooled_b = align256((size_t)(n_q_blocks + n_k_blocks) * D * 4);
+  const size_t rows_b = align256((size_t)BH * n_tq * Tk * 4);
+  const size_t cols_b = align256((size_t)BH * Tq * n_tk * 4);
   void* ws = nullptr;
-  if (int rc = sa_get_scratch(pooled_b + 2 * slice_b, stream, &ws)) return rc;
+  if (int rc = sa_get_scratch(pooled_b + rows_b + cols_b, stream, &ws)) return rc;
   float* pooled = (float*)ws;
   float* text_rows = (float*)((char*)ws + pooled_b);
-  float* text_cols = (float*)((char*)ws + pooled_b + slice_b);
+  float* text_cols = (float*)((char*)ws + pooled_b + rows_b);
 
-  const int row_bytes = (T + 7) / 8;
+  const int row_bytes = (Tk + 7) / 8;
   const float scale = (float)(1.0 / sqrt((double)D));
-  const int groups = (T + kMapRows - 1) / kMapRows;
-  const int T_pad = (T + 3) & ~3;
+  const int groups = (Tq + kMapRows - 1) / kMapRows;
+  const int T_pad = (Tk + 3) & ~3;
   const size_t map_lds = ((size_t)kMapRows * D + (size_t)kChunk * (D + 4) + (size_t)kMapRows * T_pad) * 4;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::once_flag attr_once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(attr_once, [] {
     constexpr int kMaxLds = (kMapRows * 128 + kChunk * 132 + kMapRows * kMaxBlocks) * 4;
-    HIP_TRY(hipFuncSetAttribute((const void*)map_rows<128>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds));
-    HIP_TRY(hipFuncSetAttribute((const void*)map_rows<64>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds));
-    attr_set = true;
-  }
+    attr_err = hipFuncSetAttribute((const void*)map_rows<128>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+    if (attr_err == hipSuccess)
+      attr_err = hipFuncSetAttribute((const void*)map_rows<64>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+  });
+  if (attr_err != hipSuccess)
+    return sa_fail(SPARSE_ATTN_ERR_HIP, "hipFuncSetAttribute(map_rows) failed: %s", hipGetErrorString(attr_err));
+  const unsigned pool_grid = (unsigned)(BH * (Tq > Tk ? Tq : Tk));
   if (D == 128) {
-    hipLaunchKernelGGL(pool_blocks<128>, dim3((unsigned)n_blocks, 2), dim3(256), 0, stream, (const uint16_t*)Q,
-                       (const uint16_t*)K, pooled, block, T, L, n_blocks);
+    hipLaunchKernelGGL(pool_blocks<128>, dim3(pool_grid, 2), dim3(256), 0, stream, (const uint16_t*)Q,
+                       (const uint16_t*)K, pooled, pool_q, pool_k, Tq, Tk, L, n_q_blocks);
     HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(map_rows<128>, dim3((unsigned)(B * H * groups)), dim3(256), map_lds, stream, pooled, n_blocks, T, T_pad, n_t,
-                       row_bytes, scale, tau_kv, kv_mask, text_rows, text_cols);
+    hipLaunchKernelGGL(map_rows<128>, dim3((unsigned)(BH * groups)), dim3(256), map_lds, stream, pooled, n_q_blocks, Tq, Tk,
+                       T_pad, n_tq, n_tk, row_bytes, scale, tau_kv, kv_mask, text_rows, text_cols);
   } else {
-    hipLaunchKernelGGL(pool_blocks<64>, dim3((unsigned)n_blocks, 2), dim3(256), 0, stream, (const uint16_t*)Q,
-                       (const uint16_t*)K, pooled, block, T, L, n_blocks);
+    hipLaunchKernelGGL(pool_blocks<64>, dim3(pool_grid, 2), dim3(256), 0, stream, (const uint16_t*)Q,
+                       (const uint16_t*)K, pooled, pool_q, pool_k, Tq, Tk, L, n_q_blocks);
     HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(map_rows<64>, dim3((unsigned)(B * H * groups)), dim3(256), map_lds, stream, pooled, n_blocks, T, T_pad, n_t,
-                       row_bytes, scale, tau_kv, kv_mask, text_rows, text_cols);
+    hipLaunchKernelGGL(map_rows<64>, dim3((unsigned)(BH * groups)), dim3(256), map_lds, stream, pooled, n_q_blocks, Tq, Tk,
+                       T_pad, n_tq, n_tk, row_bytes, scale, tau_kv, kv_mask, text_rows, text_cols);
   }
   HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(select_blocks, dim3((unsigned)(B * H)), dim3(256), 0, stream, text_rows, text_cols, T, n_t, tau_c,
-                     s_q, cache_flags);
+  hipLaunchKernelGGL(select_blocks, dim3((unsigned)BH), dim3(256), 0, stream, text_rows, text_cols, Tq, Tk, n_tq, n_tk,
+                     pool_q, pool_k, L, tau_c, s_q, cache_flags);
   HIP_TRY(hipGetLastError());
   return 0;
+}
+
+int sparse_symbols_update_stream(const void* Q, const void* K, uint8_t* cache_flags, uint8_t* kv_mask, int B, int H,
+                                 int L, int D, int block, int text_tokens, float tau_c, float tau_kv, float s_q,
+                                 void* hip_stream) {
+  return sparse_symbols_update_granular(Q, K, cache_flags, kv_mask, B, H, L, D, block, block, 1, text_tokens, tau_c, tau_kv,
+                                        s_q, hip_stream);
 }
 
 int sparse_symbols_update(const void* Q, const void* K, uint8_t* cache_flags, uint8_t* kv_mask, int B, int H, int L,

@@ -152,8 +152,8 @@ def _symbols(B=1, H=1, L=512, D=128, blk=128, text=128, tau_c=0.5, tau_kv=0.1, s
 
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), -1), (dict(H=0), -1), (dict(L=0), -1), (dict(D=0), -1), (dict(blk=0), -1),
-    (dict(text=64), -1),                                    # text length not a multiple of the block
-    (dict(text=0), -1), (dict(text=512), -1),               # no text blocks / no vision blocks
+    (dict(text=400), -1),                                   # ceil(400 / 128) = 4 text blocks of 4: no vision block left
+    (dict(text=0), -1), (dict(text=512), -1),               # no text tokens / no vision tokens
     (dict(D=96), -2), (dict(blk=32), -2),
     (dict(L=128 * 2049, text=128), -2),                      # more blocks than the kernels are sized for
     (dict(tau_c=-0.1), -1), (dict(tau_c=1.5), -1), (dict(tau_kv=float("nan")), -1), (dict(s_q=2.0), -1),
@@ -163,6 +163,21 @@ def _symbols(B=1, H=1, L=512, D=128, blk=128, text=128, tau_c=0.5, tau_kv=0.1, s
 def test_symbols_argument_validation_precedes_any_device_work(kw, code):
     assert _symbols(**kw) == code
     assert pkg.sparse_attn_last_error() != ""
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n=0), -1), (dict(n=65), -1), (dict(bk=32), -2), (dict(bq=256), -2),
+    (dict(n=4, L=1024, text=600), -1),                      # pooled blocks of 512 tokens: both query blocks hold text
+    (dict(n=2, bk=64, L=512, text=300), -1),                # 256-token query blocks: ceil(300 / 256) = 2 of 2 are text
+    (dict(n=16, L=128 * 16 * 2049, text=128), -2),          # more pooled blocks than the kernels are sized for
+])
+def test_granular_symbols_argument_validation(kw, code):
+    a = dict(B=1, H=1, L=512, D=128, bq=128, bk=128, n=1, text=128)
+    a.update(kw)
+    rc = pkg.load_library().sparse_symbols_update_granular(
+        FAKE, ctypes.c_void_p(0x20000000), ctypes.c_void_p(0x30000000), ctypes.c_void_p(0x40000000), a["B"], a["H"],
+        a["L"], a["D"], a["bq"], a["bk"], a["n"], a["text"], 0.5, 0.1, 0.0, None)
+    assert rc == code and pkg.sparse_attn_last_error() != ""
 
 
 def _ptr_array(vals):

@@ -242,12 +242,10 @@ def test_config3_image_cache_and_skip():
 def test_score_ranges_that_force_the_exponent_reference_to_move(profile):
     """The kernel exponentiates against a lazily updated reference.  Keys whose scale changes along the sequence
     make later scores exceed (growing, spiky), fall far below (shrinking) or overflow (huge) what the reference was
-    set to.  The bar for N(0,1) inputs does not apply as it stands: the kernel rounds the pre-scaled queries to bf16,
-    which moves a score s by about |s| 2^-9, so with a score spread three times that of N(0,1) inputs single weights
-    move by a few per cent (a CPU model of just that rounding gives max-abs 1.2e-2 on the growing profile).  Moderate
-    profiles are held to max-abs 4e-2 / mean-abs 2e-3 against the oracle; for scores in the hundreds the check is
-    the one that no rounding can break: identical value rows must be reproduced (weights sum to one, nothing
-    overflows)."""
+    set to.  The queries enter the matrix instructions as stored and the 1/sqrt(D) scale is applied to the fp32 score,
+    so these profiles, whose score spread is three times that of N(0,1) inputs, are held to the same bar as everything
+    else: max-abs 1e-2 / mean-abs 1e-3 against the oracle.  For scores in the hundreds the check is the one that no
+    rounding can break: identical value rows must be reproduced (weights sum to one, nothing overflows)."""
     B, H, L, D, bq, bk = 1, 2, 2048, 128, 128, 128
     w = synth.random_case(synth.BASE_SEED + 300, B, H, L, D, bq, bk, keep=0.7)
     Kf = synth.bf16_bits_to_f32(w.K)
@@ -270,7 +268,7 @@ def test_score_ranges_that_force_the_exponent_reference_to_move(profile):
         ref, _ = oracle_full(w)
         err = np.abs(got - ref)
         print(f"[parity] score profile {profile}: max-abs {err.max():.3e} mean-abs {err.mean():.3e}", flush=True)
-        assert err.max() <= 4e-2 and err.mean() <= 2e-3
+        assert err.max() <= 1e-2 and err.mean() <= 1e-3
     row = synth.bf16_bits_to_f32(w.V[0, 0, 0])
     w.V = np.broadcast_to(w.V[0, 0, 0], w.V.shape).copy()
     got = synth.bf16_bits_to_f32(DeviceCase(w).run())

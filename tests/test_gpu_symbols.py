@@ -137,3 +137,81 @@ def test_short_last_block(L, D, block, text):
     ref = oracle.update_symbols(Q, K, block, text, tau_c, tau_kv)
     flags, mask = run_gpu(Q, K, block, text, tau_c, tau_kv)
     compare(ref, flags, mask, T, f"ragged L{L}_D{D}_b{block}", max_ambiguous=0.05)
+
+
+def run_gpu_granular(Q, K, bq, bk, n, text, tau_c, tau_kv, s_q=0.0):
+    B, H, L, D = Q.shape
+    Tq, Tk = -(-L // (n * bq)), -(-L // (n * bk))
+    flags = torch.full((B, H, Tq), 0xAA, dtype=torch.uint8, device=dev())
+    mask = torch.full((B, H, Tq, (Tk + 7) // 8), 0xAA, dtype=torch.uint8, device=dev())
+    pkg.sparse_symbols_update(up_bf16(Q), up_bf16(K), flags, mask, bq, text, tau_c, tau_kv, s_q, block_k=bk, granularity=n)
+    torch.cuda.synchronize()
+    return flags, mask
+
+
+@pytest.mark.parametrize("L,D,bq,bk,n,text", [
+    (4096, 128, 128, 128, 2, 256),        # pooled blocks of 256 tokens: 16 x 16 symbols
+    (6000, 128, 128, 128, 3, 500),        # 384-token pooled blocks, short last one, text ends inside a pooled block
+    (4096, 64, 64, 128, 1, 256),          # b_q != b_k: 64 x 32 map, the contribution metric is carried over
+    (5000, 128, 128, 64, 2, 300),         # b_q = 2 b_k with granularity 2, nothing lines up
+    (16640, 64, 64, 64, 4, 512),          # 65 pooled blocks of 256 tokens
+])
+def test_granular_symbols_match_oracle(L, D, bq, bk, n, text):
+    """Section 3.3 with granularity n and b_q != b_k: maps of ceil(L/(n b_q)) x ceil(L/(n b_k)) pooled blocks."""
+    B, H = 1, 2
+    tau_c, tau_kv = f32(0.5), f32(0.2)
+    pool = n * max(bq, bk)
+    Lp = -(-L // pool) * pool
+    Q, K = synth.structured_qk(synth.BASE_SEED + 900 + L + n, B, H, Lp, D, n * min(bq, bk))
+    Q, K = np.ascontiguousarray(Q[:, :, :L]), np.ascontiguousarray(K[:, :, :L])
+    ref = oracle.update_symbols(Q, K, bq, text, tau_c, tau_kv, block_k=bk, granularity=n)
+    flags, mask = run_gpu_granular(Q, K, bq, bk, n, text, tau_c, tau_kv)
+    Tk = -(-L // (n * bk))
+    mask_h = mask.cpu().numpy()
+    if Tk % 8:
+        assert (mask_h[..., -1] & ((1 << (8 - Tk % 8)) - 1) == 0).all(), "padding bits set"
+    # (with b_k = 2 b_q two neighbouring query blocks inherit the same contribution: exact ties, which the oracle
+    # reports as undecidable although both sides break them by index; identical symbols are required regardless)
+    compare_symbols(ref, flags.cpu().numpy(), oracle.unpack_symbols(mask_h, Tk), f"granular L{L} {bq}x{bk} n{n}",
+                    max_ambiguous=0.05 if bq >= bk else 0.2, require_identical=True)
+    assert (flags.cpu().numpy()[..., : -(-text // (n * bq))] == 0).all()
+
+
+@pytest.mark.parametrize("L,D,bq,bk,n,text", [(4096, 128, 128, 128, 2, 256), (3000, 64, 64, 128, 3, 200)])
+def test_granular_symbols_drive_the_plan_they_were_made_for(L, D, bq, bk, n, text):
+    """Update then Dispatch at granularity n: sparse_symbols_update writes exactly the arrays that
+    sparse_attn_plan_create reads, and the attention they drive matches the oracle run on the oracle's own symbols
+    expanded to tiles."""
+    B, H = 1, 2
+    tau_c, tau_kv = f32(0.4), f32(0.3)
+    pool = n * max(bq, bk)
+    Lp = -(-L // pool) * pool
+    Q, K = synth.structured_qk(synth.BASE_SEED + 950 + L, B, H, Lp, D, n * min(bq, bk))
+    Q, K = np.ascontiguousarray(Q[:, :, :L]), np.ascontiguousarray(K[:, :, :L])
+    rng = np.random.default_rng(synth.BASE_SEED + 951)
+    V, Oc = synth.normal_bf16(rng, Q.shape), synth.normal_bf16(rng, Q.shape)
+    ref = oracle.update_symbols(Q, K, bq, text, tau_c, tau_kv, block_k=bk, granularity=n)
+    flags, mask = run_gpu_granular(Q, K, bq, bk, n, text, tau_c, tau_kv)
+    Tq, Tk = -(-L // bq), -(-L // bk)
+    sTk = -(-L // (n * bk))
+    assert (flags.cpu().numpy() == ref["cache_flags"]).all()
+    assert (oracle.unpack_symbols(mask.cpu().numpy(), sTk) == ref["M_s"]).all()
+    assert ref["cache_flags"].any() and not ref["cache_flags"].all()
+    plan = pkg.SparseAttnPlan(flags, mask, B, H, L, bq, bk, granularity=n)
+    dQ, dK, dV, dOc = up_bf16(Q), up_bf16(K), up_bf16(V), up_bf16(Oc)
+    O = torch.zeros_like(dQ)
+    plan.run(dQ, dK, dV, dOc, O)
+    torch.cuda.synchronize()
+    f, m = oracle.expand_granularity(ref["cache_flags"], ref["M_s"], n, Tq, Tk)
+    ref_o, ref_bits = oracle.sparse_attention(Q, K, V, f, oracle.pack_symbols(m), Oc, bq, bk)
+    got = down_bits(O)
+    c = np.repeat(f != 0, bq, axis=2)[:, :, :L]
+    assert (got[c] == Oc[c]).all(), "cached blocks are not bit exact"
+    # The block-structured queries and keys make the softmax peaked, so outputs are single V rows of magnitude up to
+    # 4 rather than averages: the bf16 rounding of the output alone is then up to 2^-7 = 7.8e-3 (half a unit in the
+    # last place in [2, 4)), and the unit-variance tolerance applies relative to the magnitude of the value.
+    err = np.abs(synth.bf16_bits_to_f32(got).astype(np.float64) - ref_o)[~c]
+    bound = 1e-2 * np.maximum(1.0, np.abs(ref_o[~c]))
+    print(f"[parity] update->dispatch at granularity {n}: max-abs {err.max():.3e} mean-abs {err.mean():.3e}", flush=True)
+    assert (err <= bound).all() and err.mean() <= 1e-3
+    plan.destroy()
