@@ -314,6 +314,23 @@ def main():
             log(f"gemm_o stage 2 cached {sfrac:.2f}: {ms:.3f} ms, {go[-1]['speedup_vs_dense']:.2f}x; over N=6 steps "
                 f"{go[-1]['aggregated_speedup_N6']:.2f}x (model {go[-1]['model_speedup_N6']:.2f}x)")
         extra["gemm_o"] = go
+        # the Dispatch-step form: output initialised by a first-order OP_reuse(B_c) inside the same kernel (two stored
+        # terms read instead of one addend), at the last cached fraction above
+        Bd0 = torch.randn((w.B, w.L, C), device=dev, generator=g).to(torch.bfloat16)
+        for _ in range(2):
+            pkg.sparse_gemm_o_reuse(Q, Wo, None, fl, [Bc, Bd0], [1.0, 2.0], Yo, w.block_q)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            pkg.sparse_gemm_o_reuse(Q, Wo, None, fl, [Bc, Bd0], [1.0, 2.0], Yo, w.block_q)
+        e1.record()
+        torch.cuda.synchronize()
+        extra["gemm_o_fused_reuse"] = dict(cached_frac=go[-1]["cached_frac"], n_terms=2, ms=e0.elapsed_time(e1) / 10,
+                                           hbm_bytes=3 * Yo.numel() * 2)
+        log(f"gemm_o stage 2 with a two-term OP_reuse(B_c) fused, cached {go[-1]['cached_frac']:.2f}: "
+            f"{extra['gemm_o_fused_reuse']['ms']:.3f} ms")
+        del Bd0
         # OP_reuse(B_c) as the stand-alone element-wise kernel: Yo = 1 * B_c + 2 * B_c' (first-order forecast)
         Bd = torch.randn((w.B, w.L, C), device=dev, generator=g).to(torch.bfloat16)
         for _ in range(2):
@@ -404,8 +421,8 @@ def main():
         def dispatch_step(plan, k):
             pkg.sparse_gemm_q_norm_rope(Xp, Wq, None, gain, 1e-6, rc, rs, dfl, Q2, w.block_q)
             plan.run(Q2, K, V, None, O)
-            pkg.sparse_op_reuse(termsB, pkg.sparse_taylor_coefficients(order, float(k)), add)
-            pkg.sparse_gemm_o(O, Wo, None, dfl, 0, add, Yo, w.block_q)
+            # output initialised by OP_reuse(B_c), computed heads added, in one kernel
+            pkg.sparse_gemm_o_reuse(O, Wo, None, dfl, termsB, pkg.sparse_taylor_coefficients(order, float(k)), Yo, w.block_q)
 
         def timed(fn, reps):
             torch.cuda.synchronize()

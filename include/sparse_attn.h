@@ -211,6 +211,21 @@ int sparse_gemm_o(const void* O, const void* W, const void* bias, const uint8_t*
 int sparse_gemm_o_stream(const void* O, const void* W, const void* bias, const uint8_t* cache_flags,
                          int select_cached, const void* addend, void* Out, int B, int H, int L, int D, int C_out,
                          int block_q, void* hip_stream);
+/*
+ * Stage 2 of GEMM-O at a Dispatch step with the output "initialised by OP_reuse(B_c)" (Section 3.5) in one call:
+ *     Out = OP_reuse(B_c terms) + bias + sum over the heads whose flag is clear of O^h . W^h
+ * with OP_reuse(terms) = sum_d coef[d] * terms[d] as defined for sparse_op_reuse below (fp32 sum in term order,
+ * rounded to bf16 once, then used as the addend): the result is bit-identical to sparse_op_reuse into a buffer
+ * followed by sparse_gemm_o(..., select_cached = 0, addend = that buffer), without writing the forecast bias to
+ * memory and reading it back.
+ *   terms    HOST array of n_terms (1..4) DEVICE pointers, each bf16 [B, L, C_out], 16-byte aligned; a term may be
+ *            Out itself (in place), otherwise it must not overlap Out
+ *   coef     HOST array of n_terms finite weights (sparse_taylor_coefficients)
+ * Everything else as for sparse_gemm_o_stream.  Allocates nothing.
+ */
+int sparse_gemm_o_reuse(const void* O, const void* W, const void* bias, const uint8_t* cache_flags,
+                        const void* const* terms, const float* coef, int n_terms, void* Out, int B, int H, int L, int D,
+                        int C_out, int block_q, void* hip_stream);
 
 /*
  * OP_reuse as a Taylor-series forecast (Section 3.3: cached blocks are forecast from stored features and their

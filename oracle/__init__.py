@@ -14,7 +14,7 @@ example, textbook dense attention, closed forms, brute force).  Numerical parity
 the authors' own kernel is unpinned: the paper prints no attention outputs.
 """
 from .gemm_q import gemm_q, rms_norm, rope, computed_flops as gemm_q_flops  # noqa: F401
-from .gemm_o import gemm_o, reduced_heads as gemm_o_segments, speedup_model as gemm_o_speedup_model  # noqa: F401
+from .gemm_o import gemm_o, gemm_o_reuse, reduced_heads as gemm_o_segments, speedup_model as gemm_o_speedup_model  # noqa: F401
 from .op_reuse import taylor_coefficients, taylor_update, op_reuse, attention_with_forecast  # noqa: F401
 from .symbols import (  # noqa: F401
     update_symbols, compressed_map, caching_metrics, cached_set, skipped_set, contribution_on_query_axis,

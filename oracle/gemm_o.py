@@ -45,6 +45,16 @@ def gemm_o(O, W, bias, cache_flags, select, addend, block_q):
     return out, _narrow(out)
 
 
+def gemm_o_reuse(O, W, bias, cache_flags, terms, coef, block_q):
+    """Stage 2 at a Dispatch step as Section 3.5 words it, "output initialised by OP_reuse(B_c)" and then the heads
+    that were really computed accumulated onto it:  Out = OP_reuse(terms of B_c) + bias + sum over heads with the flag
+    clear.  OP_reuse is the Taylor sum of op_reuse.op_reuse (whose result is a stored bf16 tensor, rounded once, as
+    the cached bias itself is); it then plays the part of the addend of gemm_o."""
+    from .op_reuse import op_reuse
+    _, forecast_bits = op_reuse(terms, coef)
+    return gemm_o(O, W, bias, cache_flags, 0, forecast_bits, block_q)
+
+
 def reduced_heads(cache_flags, select, B, H, Tq):
     """Number of (b, i, h) reduction segments a call with this selection visits."""
     if cache_flags is None:

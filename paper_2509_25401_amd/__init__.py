@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     sparse_attn_fwd_timed,
     sparse_gemm_q,
     sparse_gemm_o,
+    sparse_gemm_o_reuse,
     SparseAttnPlan,
     sparse_gemm_q_norm_rope,
     sparse_symbols_update,

@@ -68,6 +68,8 @@ def load_library():
     lib.sparse_gemm_o.restype = i32
     lib.sparse_gemm_o_stream.argtypes = [vp] * 4 + [i32, vp, vp] + [i32] * 6 + [vp]
     lib.sparse_gemm_o_stream.restype = i32
+    lib.sparse_gemm_o_reuse.argtypes = [vp] * 4 + [vp, vp, i32, vp] + [i32] * 6 + [vp]
+    lib.sparse_gemm_o_reuse.restype = i32
     f32 = ctypes.c_float
     lib.sparse_attn_fwd_forecast.argtypes = [vp] * 7 + [i32, vp] + [i32] * 6 + [vp]
     lib.sparse_attn_fwd_forecast.restype = i32
@@ -322,6 +324,29 @@ def sparse_gemm_o(O, W, bias, cache_flags, select_cached, addend, Out, block_q, 
                                              _dev_ptr(cache_flags, "cache_flags", True), int(select_cached),
                                              _dev_ptr(addend, "addend", True), _dev_ptr(Out, "Out"),
                                              int(B), int(H), int(L), int(D), int(C_out), int(block_q), _stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
+    return Out
+
+
+def sparse_gemm_o_reuse(O, W, bias, cache_flags, terms, coef, Out, block_q, stream=None):
+    """GEMM-O stage 2 with the output initialised by OP_reuse(B_c) in one call: Out = sum_d coef[d] * terms[d] (rounded
+    to bf16 once) + bias + the heads whose flag is clear.  terms: list of device tensors bf16 [B,L,C_out] (a term may
+    be Out); bit-identical to sparse_op_reuse followed by sparse_gemm_o with that result as the addend."""
+    import torch
+    B, H, L, D = (int(x) for x in O.shape)
+    C_out = int(W.shape[0])
+    _check(O, "O", torch.bfloat16, (B, H, L, D))
+    _check(W, "W", torch.bfloat16, (C_out, H * D))
+    _check(Out, "Out", torch.bfloat16, (B, L, C_out))
+    _check(bias, "bias", torch.bfloat16, (C_out,), allow_none=True)
+    _check(cache_flags, "cache_flags", torch.uint8, (B, H, _ceil_div(L, block_q)), allow_none=True)
+    for n, t in enumerate(terms):
+        _check(t, f"terms[{n}]", torch.bfloat16, (B, L, C_out))
+    ptrs, cf = _term_arrays(terms, coef, "terms")
+    rc = load_library().sparse_gemm_o_reuse(_dev_ptr(O, "O"), _dev_ptr(W, "W"), _dev_ptr(bias, "bias", True),
+                                            _dev_ptr(cache_flags, "cache_flags", True), ptrs, cf, len(terms),
+                                            _dev_ptr(Out, "Out"), B, H, L, D, C_out, int(block_q), _stream_ptr(stream))
     if rc != 0:
         _raise(rc)
     return Out

@@ -899,12 +899,14 @@ bool overlaps(const void* a, const void* b, size_t bytes) {
 template <int D, int BQ, int BK, bool RAGGED>
 int launch_attn_variant(const AttnParams& p, int grid, hipStream_t stream) {
   constexpr size_t lds = 4 * (size_t)kKeys * D * 2 + 16;
-  static bool attr_set = false;
-  if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute((const void*)attn_kernel<D, BQ, BK, RAGGED>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
+  static std::once_flag once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(once, [] {
+    attr_err = hipFuncSetAttribute((const void*)attn_kernel<D, BQ, BK, RAGGED>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)lds);
+  });
+  if (attr_err != hipSuccess)
+    return fail(SPARSE_ATTN_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(attr_err));
   hipLaunchKernelGGL((attn_kernel<D, BQ, BK, RAGGED>), dim3(grid), dim3(BQ * 2), lds, stream, p);
   HIP_TRY(hipGetLastError());
   return 0;

@@ -9,12 +9,18 @@
 // walks a bitmap of that token block's selected heads (built with one wave ballot, walked with
 // scalar find-first-set) and never loads the O or W columns of the others.
 //
+// The addend may also be given as the stored terms of the cached bias and their weights: the kernel then forms
+// OP_reuse(B_c) = sum_d coef[d] * terms[d] itself while it fetches them (fp32, term order, rounded to bf16 exactly
+// as the stand-alone element-wise kernel rounds it), so a Dispatch step needs no separate pass that writes the
+// forecast bias and reads it back.  A token block none of whose heads is selected only streams: addend + bias.
+//
 // One workgroup per (token block, 128 output channels) tile; transposed MFMA product as in the
 // query projection (A = weight rows, B = token rows, both k-contiguous in LDS), direct-to-LDS
 // loads, 64 reduction channels per stage, double buffered.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "sparse_attn.h"
@@ -34,15 +40,20 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kStepK = 64;                 // reduction channels per LDS stage
 constexpr int kRowB = kStepK * 2;          // bytes per tile row in LDS
 constexpr int kBN = 128;                   // output channels per workgroup
+constexpr int kMaxTerms = 4;               // stored feature + up to three derivatives
 
 struct GemmOParams {
   const char* O;         // bf16 [B, H, L, D]
   const char* W;         // bf16 [C_out, H*D]
   const uint16_t* bias;  // bf16 [C_out] or nullptr
   const uint8_t* flags;  // [B, H, Tq] or nullptr
-  const char* addend;    // bf16 [B, L, C_out] or nullptr
+  const char* addend;    // bf16 [B, L, C_out] or nullptr; with n_terms > 0: the first term
   char* Out;             // bf16 [B, L, C_out]
   int H, L, Tq, C_out, select;
+  // OP_reuse of the cached bias fused into the addend: addend = sum_d coef[d] * term[d], term[0] = `addend`
+  const char* term[kMaxTerms - 1];
+  float coef[kMaxTerms];
+  int n_terms;           // 0: `addend` is taken as it is
 };
 
 __device__ __forceinline__ int row_swizzle(int row) { return (row >> 1) & 7; }
@@ -174,6 +185,72 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
 #pragma unroll
     for (int it = 0; it < OUT_ITERS; ++it)
       if (it * (NT / 16) + tid / 16 < rows_valid) add_bits[it] = *(const u32x4*)(p.addend + out_offset(it));
+    if (p.n_terms > 0) {
+      // OP_reuse(B_c): fp32 sum of the scaled terms in term order, one rounding to bf16 (what the element-wise
+      // kernel computes), kept packed like a plain addend
+#pragma unroll
+      for (int it = 0; it < OUT_ITERS; ++it) {
+        if (it * (NT / 16) + tid / 16 >= rows_valid) continue;
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          v[2 * e] = p.coef[0] * bf16_bits_to_float(add_bits[it][e] & 0xffffu);
+          v[2 * e + 1] = p.coef[0] * bf16_bits_to_float(add_bits[it][e] >> 16);
+        }
+        for (int d = 1; d < p.n_terms; ++d) {
+          const u32x4 tb = *(const u32x4*)(p.term[d - 1] + out_offset(it));
+          const float cd = p.coef[d];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[2 * e] = fmaf(cd, bf16_bits_to_float(tb[e] & 0xffffu), v[2 * e]);
+            v[2 * e + 1] = fmaf(cd, bf16_bits_to_float(tb[e] >> 16), v[2 * e + 1]);
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          bf16x2 pr;
+          pr[0] = (__bf16)v[2 * e];
+          pr[1] = (__bf16)v[2 * e + 1];
+          add_bits[it][e] = __builtin_bit_cast(unsigned, pr);
+        }
+      }
+    }
+  }
+
+  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (p.bias) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bv[e] = bf16_bits_to_float(p.bias[col * kBN + out_g * 8 + e]);
+  }
+  // accumulated channels v[0..7] of one token + bias + addend -> 16 bytes of bf16
+  auto finish = [&](int it, float (&v)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += bv[e];
+    if (p.addend) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[2 * e] += bf16_bits_to_float(add_bits[it][e] & 0xffffu);
+        v[2 * e + 1] += bf16_bits_to_float(add_bits[it][e] >> 16);
+      }
+    }
+    u32x4 pk;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      bf16x2 pr;
+      pr[0] = (__bf16)v[2 * e];
+      pr[1] = (__bf16)v[2 * e + 1];
+      pk[e] = __builtin_bit_cast(unsigned, pr);
+    }
+    if (it * (NT / 16) + tid / 16 < rows_valid) *(u32x4*)(p.Out + out_offset(it)) = pk;
+  };
+  if (heads == 0ull) {
+    // no head of this token block is selected: the tile is addend + bias, straight from registers
+#pragma unroll
+    for (int it = 0; it < OUT_ITERS; ++it) {
+      float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      finish(it, v);
+    }
+    return;
   }
 
   // scalar walk over the selected heads, PARTS stages per head
@@ -225,12 +302,7 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
         *(f32x4*)(smem + token * 512 + ((chunk ^ (token & 31)) * 16)) = v;
       }
   __syncthreads();
-  // part 2: row-contiguous read back, + addend + bias, round to bf16, 16-byte stores
-  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (p.bias) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) bv[e] = bf16_bits_to_float(p.bias[col * kBN + out_g * 8 + e]);
-  }
+  // part 2: row-contiguous read back, + bias + addend, round to bf16, 16-byte stores
 #pragma unroll
   for (int it = 0; it < OUT_ITERS; ++it) {
     const int token = it * (NT / 16) + tid / 16;
@@ -239,25 +311,10 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
     float v[8];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      v[e] = v0[e] + bv[e];
-      v[4 + e] = v1[e] + bv[4 + e];
+      v[e] = v0[e];
+      v[4 + e] = v1[e];
     }
-    if (p.addend) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        v[2 * e] += bf16_bits_to_float(add_bits[it][e] & 0xffffu);
-        v[2 * e + 1] += bf16_bits_to_float(add_bits[it][e] >> 16);
-      }
-    }
-    u32x4 pk;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      bf16x2 pr;
-      pr[0] = (__bf16)v[2 * e];
-      pr[1] = (__bf16)v[2 * e + 1];
-      pk[e] = __builtin_bit_cast(unsigned, pr);
-    }
-    if (token < rows_valid) *(u32x4*)(p.Out + out_offset(it)) = pk;
+    finish(it, v);
   }
 }
 
@@ -265,13 +322,13 @@ template <int BQ, int D>
 int launch(const GemmOParams& p, int tiles, hipStream_t stream) {
   constexpr size_t lds = 2 * (size_t)(kBN + BQ) * kRowB;
   constexpr int threads = (BQ / 64) * 2 * 64;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_o_kernel<BQ, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds);
-    if (e != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
-    attr_set = true;
-  }
+  static std::once_flag once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(once, [] {
+    attr_err = hipFuncSetAttribute((const void*)gemm_o_kernel<BQ, D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  });
+  if (attr_err != hipSuccess)
+    return sa_fail(SPARSE_ATTN_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(attr_err));
   hipLaunchKernelGGL((gemm_o_kernel<BQ, D>), dim3(tiles), dim3(threads), lds, stream, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "gemm_o launch failed: %s", hipGetErrorString(e));
@@ -285,11 +342,11 @@ bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
 
 }  // namespace
 
-extern "C" {
+namespace {
 
-int sparse_gemm_o_stream(const void* O, const void* W, const void* bias, const uint8_t* cache_flags,
-                         int select_cached, const void* addend, void* Out, int B, int H, int L, int D, int C_out,
-                         int block_q, void* hip_stream) {
+int gemm_o_run(const void* O, const void* W, const void* bias, const uint8_t* cache_flags, int select_cached,
+               const void* addend, const void* const* terms, const float* coef, int n_terms, void* Out, int B, int H,
+               int L, int D, int C_out, int block_q, hipStream_t stream) {
   if (B <= 0 || H <= 0 || L <= 0 || D <= 0 || C_out <= 0 || block_q <= 0)
     return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: sizes must be positive (B=%d H=%d L=%d D=%d C_out=%d block_q=%d)",
                    B, H, L, D, C_out, block_q);
@@ -325,16 +382,56 @@ int sparse_gemm_o_stream(const void* O, const void* W, const void* bias, const u
   p.Tq = tq;
   p.C_out = C_out;
   p.select = select_cached;
-  hipStream_t stream = (hipStream_t)hip_stream;
+  p.n_terms = 0;
+  for (int d = 0; d < kMaxTerms; ++d) p.coef[d] = 0.f;
+  for (int d = 0; d + 1 < kMaxTerms; ++d) p.term[d] = nullptr;
+  if (terms) {
+    if (n_terms < 1 || n_terms > kMaxTerms)
+      return sa_fail(SPARSE_ATTN_ERR_UNSUPPORTED, "gemm_o: n_terms=%d must be between 1 and %d", n_terms, kMaxTerms);
+    if (!coef) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: coef must not be NULL");
+    for (int d = 0; d < n_terms; ++d) {
+      if (!terms[d]) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: terms[%d] must not be NULL", d);
+      if ((uintptr_t)terms[d] & 15) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: terms[%d] must be 16-byte aligned", d);
+      if (terms[d] != Out && ranges_overlap(Out, outb, terms[d], outb))
+        return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: terms[%d] must be Out itself or must not overlap Out", d);
+      if (!(coef[d] == coef[d]) || coef[d] - coef[d] != 0.f)
+        return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: coef[%d] must be finite", d);
+    }
+    p.addend = (const char*)terms[0];
+    if (!(n_terms == 1 && coef[0] == 1.0f)) {      // one term with weight 1 is the plain addend
+      p.n_terms = n_terms;
+      for (int d = 0; d < n_terms; ++d) p.coef[d] = coef[d];
+      for (int d = 1; d < n_terms; ++d) p.term[d - 1] = (const char*)terms[d];
+    }
+  }
   if (block_q == 128 && D == 128) return launch<128, 128>(p, (int)tiles, stream);
   if (block_q == 128 && D == 64) return launch<128, 64>(p, (int)tiles, stream);
   if (block_q == 64 && D == 128) return launch<64, 128>(p, (int)tiles, stream);
   return launch<64, 64>(p, (int)tiles, stream);
 }
 
+}  // namespace
+
+extern "C" {
+
+int sparse_gemm_o_stream(const void* O, const void* W, const void* bias, const uint8_t* cache_flags,
+                         int select_cached, const void* addend, void* Out, int B, int H, int L, int D, int C_out,
+                         int block_q, void* hip_stream) {
+  return gemm_o_run(O, W, bias, cache_flags, select_cached, addend, nullptr, nullptr, 0, Out, B, H, L, D, C_out, block_q,
+                    (hipStream_t)hip_stream);
+}
+
 int sparse_gemm_o(const void* O, const void* W, const void* bias, const uint8_t* cache_flags, int select_cached,
                   const void* addend, void* Out, int B, int H, int L, int D, int C_out, int block_q) {
   return sparse_gemm_o_stream(O, W, bias, cache_flags, select_cached, addend, Out, B, H, L, D, C_out, block_q, nullptr);
+}
+
+int sparse_gemm_o_reuse(const void* O, const void* W, const void* bias, const uint8_t* cache_flags,
+                        const void* const* terms, const float* coef, int n_terms, void* Out, int B, int H, int L, int D,
+                        int C_out, int block_q, void* hip_stream) {
+  if (!terms) return sa_fail(SPARSE_ATTN_ERR_INVALID, "gemm_o: terms must not be NULL");
+  return gemm_o_run(O, W, bias, cache_flags, 0, nullptr, terms, coef, n_terms, Out, B, H, L, D, C_out, block_q,
+                    (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

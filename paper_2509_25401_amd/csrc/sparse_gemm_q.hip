@@ -12,6 +12,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "sparse_attn.h"
@@ -290,13 +291,14 @@ int launch(const GemmQParams& p, int tiles, hipStream_t stream) {
   constexpr size_t epi_lds = NORM_ROPE ? (size_t)(2 * BQ * (D / 2 + 2) + 2 * BQ) * 4 : 0;   // cos, sin tiles + row sums
   constexpr size_t lds = stage_lds > epi_lds ? stage_lds : epi_lds;
   constexpr int threads = (BQ / 64) * (D / 64) * 64;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_q_kernel<BQ, D, NORM_ROPE>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds);
-    if (e != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
-    attr_set = true;
-  }
+  static std::once_flag once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(once, [] {
+    attr_err = hipFuncSetAttribute((const void*)gemm_q_kernel<BQ, D, NORM_ROPE>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)lds);
+  });
+  if (attr_err != hipSuccess)
+    return sa_fail(SPARSE_ATTN_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(attr_err));
   hipLaunchKernelGGL((gemm_q_kernel<BQ, D, NORM_ROPE>), dim3(tiles), dim3(threads), lds, stream, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return sa_fail(SPARSE_ATTN_ERR_HIP, "gemm_q launch failed: %s", hipGetErrorString(e));

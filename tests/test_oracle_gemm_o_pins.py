@@ -110,3 +110,38 @@ def test_short_last_token_block():
     Of, Wf = bits_to_f64(O), bits_to_f64(W)
     want = Of[0, 1, 32:] @ Wf[:, D:2 * D].T
     assert np.abs(s0[0, 32:] - want).max() < 1e-12
+
+
+def test_output_initialised_by_op_reuse_is_the_composition_of_the_two_definitions():
+    """gemm_o_reuse: OP_reuse(B_c) then stage 2.  Pinned by special cases with known answers: one term with weight
+    one is plain stage 2 with that term as the addend; weights (1, 0, ..) ignore the higher terms; with every head
+    cached and no bias the result is the rounded Taylor sum itself; and a polynomial B_c trajectory sampled at the
+    stored step and forecast k steps ahead gives stage 2 of the true B_c(k) (terms exact in bf16)."""
+    rng = np.random.default_rng(31)
+    B, H, L, D, C_out, bq = 1, 3, 64, 8, 16, 32
+    O = synth.normal_bf16(rng, (B, H, L, D))
+    W = synth.normal_bf16(rng, (C_out, H * D))
+    bias = synth.normal_bf16(rng, (C_out,))
+    flags = np.array([[[1, 0], [0, 0], [1, 1]]], dtype=np.uint8)
+    t0, t1 = synth.normal_bf16(rng, (B, L, C_out)), synth.normal_bf16(rng, (B, L, C_out))
+    plain, plain_bits = oracle.gemm_o(O, W, bias, flags, 0, t0, bq)
+    got, got_bits = oracle.gemm_o_reuse(O, W, bias, flags, [t0], [1.0], bq)
+    assert (got == plain).all() and (got_bits == plain_bits).all()
+    got, _ = oracle.gemm_o_reuse(O, W, bias, flags, [t0, t1], [1.0, 0.0], bq)
+    assert (got == plain).all()
+    allc = np.ones_like(flags)
+    got, got_bits = oracle.gemm_o_reuse(O, W, None, allc, [t0, t1], [1.0, 2.0], bq)
+    f, fb = oracle.op_reuse([t0, t1], [1.0, 2.0])
+    assert (got_bits == fb).all() and np.abs(got - helpers_bits(fb)).max() == 0.0
+    # linear trajectory with small integer values: B_c(k) = a + k * d is exact in bf16
+    a = rng.integers(-8, 8, size=(B, L, C_out)).astype(np.float32)
+    d = rng.integers(-3, 3, size=(B, L, C_out)).astype(np.float32)
+    bits = synth.f32_to_bf16_bits
+    want, _ = oracle.gemm_o(O, W, bias, flags, 0, bits(a + 3 * d), bq)
+    got, _ = oracle.gemm_o_reuse(O, W, bias, flags, [bits(a), bits(d)], oracle.taylor_coefficients(1, 3.0), bq)
+    assert np.abs(got - want).max() == 0.0
+
+
+def helpers_bits(b):
+    from helpers import bits_to_f64
+    return bits_to_f64(b)
