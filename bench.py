@@ -64,6 +64,10 @@ def main():
     ap.add_argument("--cpu-blocks", type=int, default=1280, help="query blocks in the oracle's timed sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--workload", choices=("sweep", "config4"), default="sweep",
+                    help="sweep = the headline workload (band + text + random mask at --keep, nothing cached); config4 = the "
+                         "multi-granularity video configuration (25 %% of the query blocks cached, 3-D window + text + random "
+                         "mask at 25 %% keep) as the timed case, for profiling; implies --no-extras")
     ap.add_argument("--heads", type=int, default=24, help="heads (24 = the named workload; fewer only for quick checks)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -88,7 +92,10 @@ def main():
         return None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint8)).to(dev)
 
     t0 = time.time()
-    w = synth.config_video_sweep(args.keep, H=H)
+    if args.workload == "config4":
+        args.no_extras = True
+        args.no_cpu = True
+    w = synth.config_video_sweep(args.keep, H=H) if args.workload == "sweep" else synth.config_video_multi(H=H)
     log(f"inputs drawn in {time.time() - t0:.1f}s: {w.name} B={w.B} H={w.H} L={w.L} D={w.D} blocks {w.block_q}x{w.block_k}")
     Q, K, V = up_bf16(w.Q), up_bf16(w.K), up_bf16(w.V)
     O = torch.empty_like(Q)
@@ -142,7 +149,10 @@ def main():
         del src, dst
         log("copy calibration: one 1 GiB device-to-device copy dispatched")
 
-    head = run_case(w.M_s, None, None, args.steps, args.warmup, f"headline keep={args.keep:g}")
+    if args.workload == "config4":
+        head = run_case(w.M_s, w.cache_flags, up_bf16(w.O_cache), args.steps, args.warmup, "config 4 (cache + skip, windowed mask)")
+    else:
+        head = run_case(w.M_s, None, None, args.steps, args.warmup, f"headline keep={args.keep:g}")
 
     extra = {}
     if not args.no_extras:
@@ -503,11 +513,13 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"video-DiT 33K tokens: B={w.B} H={w.H} L={w.L} D={w.D} block {w.block_q}x{w.block_k}, "
-                               f"band+text+random mask at {head['keep'] * 100:.1f}% keep, no cached blocks",
+                               + (f"band+text+random mask at {head['keep'] * 100:.1f}% keep, no cached blocks"
+                                  if args.workload == "sweep" else
+                                  f"25% of the video query blocks cached, 3-D window+text+random mask, {head['keep'] * 100:.1f}% of all pairs kept"),
                    "kept_pairs": head["kept_pairs"], "total_pairs": total_pairs},
         "roofline": {"bound": "mfma", "achieved": head["kernel_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": head["kernel_tflops"] / PEAK_BF16_TFLOPS,
-                     "traffic": measured_traffic_bytes(args.keep, H)},
+                     "traffic": measured_traffic_bytes(args.keep, H) if args.workload == "sweep" else None},
         "cpu_baseline": cpu,
         "extra": extra,
     }

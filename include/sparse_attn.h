@@ -148,13 +148,14 @@ int sparse_gemm_q_stream(const void* X, const void* W, const void* bias, const u
  * create allocates the plan's device buffer (hipMalloc) and enqueues the pre-pass on hip_stream; the symbol
  * arrays may be changed or freed once that work has run.  The plan belongs to the device that was current at
  * create.  run allocates nothing; it must be ordered after create (same stream, or synchronise), and two
- * runs of one plan must not overlap in time (they share its queue counters).  destroy waits for the device
+ * runs of one plan must not overlap in time (a run resets and consumes the plan's queue counters, which is why
+ * the plan is not const).  destroy waits for the device
  * and frees.  Errors as for sparse_attn_fwd; on failure *plan is NULL.
  */
 typedef struct sparse_attn_plan sparse_attn_plan;
 int sparse_attn_plan_create(const uint8_t* cache_flags, const uint8_t* kv_mask, int B, int H, int L, int block_q,
                             int block_k, int granularity, void* hip_stream, sparse_attn_plan** plan);
-int sparse_attn_plan_run(const sparse_attn_plan* plan, const void* Q, const void* K, const void* V, const void* O_cache,
+int sparse_attn_plan_run(sparse_attn_plan* plan, const void* Q, const void* K, const void* V, const void* O_cache,
                          void* O, int D, void* hip_stream);
 int sparse_attn_plan_destroy(sparse_attn_plan* plan);
 /*
@@ -162,7 +163,7 @@ int sparse_attn_plan_destroy(sparse_attn_plan* plan);
  * 3.2's Dispatch step with forecast features: stored symbols, stored pre-pass, cached blocks forecast from their
  * terms).  O_terms, coef, n_terms as for sparse_attn_fwd_forecast; everything else as for sparse_attn_plan_run.
  */
-int sparse_attn_plan_run_forecast(const sparse_attn_plan* plan, const void* Q, const void* K, const void* V,
+int sparse_attn_plan_run_forecast(sparse_attn_plan* plan, const void* Q, const void* K, const void* V,
                                   const void* const* O_terms, const float* coef, int n_terms, void* O, int D,
                                   void* hip_stream);
 
@@ -326,8 +327,29 @@ int sparse_symbols_update_granular(const void* Q, const void* K, uint8_t* cache_
 int sparse_attn_profile_begin(int max_calls);
 int sparse_attn_profile_end(int* calls, double* plan_ms_total, double* attn_ms_total);
 
-/* Bytes of device scratch one call of this shape uses (0 for invalid shapes). */
+/*
+ * Scratch memory of the one-shot calls.  sparse_attn_fwd, sparse_attn_fwd_stream, sparse_attn_fwd_timed,
+ * sparse_attn_fwd_forecast and sparse_symbols_update* keep one device buffer per (device, stream) inside the
+ * library: allocated on the first call on that stream (hipMalloc), grown when a later call needs more (stream
+ * synchronisation + hipFree + hipMalloc), shared by all of these calls on the stream, never shrunk.  Consequences:
+ * such a call can be captured into a HIP graph only after a call of at least the same size has run on that stream,
+ * and a graph captured from it becomes invalid if the buffer grows afterwards; the plan calls, sparse_attn_fwd_noalloc
+ * and sparse_attn_fwd_workspace have no such restriction.  sparse_attn_release_scratch waits for the stream and frees
+ * its buffer (call it before destroying a stream: the library cannot see that a stream handle has died, and a
+ * recycled handle would inherit the old buffer, which is harmless but keeps memory).
+ *
+ * sparse_attn_workspace_bytes: bytes of scratch one attention call of this shape uses (0 for invalid shapes).
+ * sparse_attn_fwd_workspace: sparse_attn_fwd_stream with that scratch supplied by the caller -- `workspace` is
+ * device memory, 256-byte aligned, of at least sparse_attn_workspace_bytes(...) bytes, used only while the call's
+ * work runs; the call allocates nothing.  Two calls that overlap in time must not share a workspace.
+ */
 size_t sparse_attn_workspace_bytes(int B, int H, int L, int block_q, int block_k);
+int sparse_attn_fwd_workspace(const void* Q, const void* K, const void* V,
+                              const uint8_t* cache_flags, const uint8_t* kv_mask,
+                              const void* O_cache, void* O,
+                              int B, int H, int L, int D, int block_q, int block_k,
+                              void* workspace, size_t workspace_size, void* hip_stream);
+int sparse_attn_release_scratch(void* hip_stream);
 
 /*
  * Pair accounting of Section 4.1 (Sparsity = skip / total over (Q_i K_j^T, P_ij V_j) pairs).

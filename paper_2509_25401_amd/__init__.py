@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     sparse_attn_fwd,
     sparse_attn_fwd_noalloc,
     sparse_attn_fwd_timed,
+    sparse_attn_fwd_workspace,
+    sparse_attn_release_scratch,
     sparse_gemm_q,
     sparse_gemm_o,
     sparse_gemm_o_reuse,

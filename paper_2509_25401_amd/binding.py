@@ -44,6 +44,10 @@ def load_library():
     lib.sparse_attn_fwd_noalloc.restype = i32
     lib.sparse_attn_fwd_timed.argtypes = fwd_args + [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
     lib.sparse_attn_fwd_timed.restype = i32
+    lib.sparse_attn_fwd_workspace.argtypes = fwd_args + [vp, ctypes.c_size_t, vp]
+    lib.sparse_attn_fwd_workspace.restype = i32
+    lib.sparse_attn_release_scratch.argtypes = [vp]
+    lib.sparse_attn_release_scratch.restype = i32
     lib.sparse_attn_workspace_bytes.argtypes = [i32] * 5
     lib.sparse_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.sparse_attn_count_kept.argtypes = [vp, vp] + [i32] * 5 + [ctypes.POINTER(ctypes.c_ulonglong)] * 2
@@ -197,6 +201,27 @@ def sparse_attn_fwd_noalloc(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, 
     if rc != 0:
         _raise(rc)
     return O
+
+
+def sparse_attn_fwd_workspace(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k, workspace, stream=None):
+    """sparse_attn_fwd with the scratch memory supplied by the caller: `workspace` is a device uint8 tensor of at
+    least sparse_attn_workspace_bytes(B, H, L, block_q, block_k) bytes, 256-byte aligned."""
+    import torch
+    args = _fwd_args(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k)
+    if workspace.dtype != torch.uint8 or workspace.dim() != 1:
+        raise ValueError("workspace must be a one-dimensional uint8 tensor")
+    rc = load_library().sparse_attn_fwd_workspace(*args, _dev_ptr(workspace, "workspace"), int(workspace.numel()),
+                                                  _stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
+    return O
+
+
+def sparse_attn_release_scratch(stream=None) -> None:
+    """Frees the library's scratch buffer of `stream` (default: torch's current stream) after waiting for it."""
+    rc = load_library().sparse_attn_release_scratch(_stream_ptr(stream))
+    if rc != 0:
+        _raise(rc)
 
 
 def sparse_attn_fwd_timed(Q, K, V, cache_flags, kv_mask, O_cache, O, block_q, block_k, stream=None):

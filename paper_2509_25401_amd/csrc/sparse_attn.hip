@@ -977,7 +977,7 @@ struct Forecast {
 int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags, const uint8_t* kv_mask,
         const void* O_cache, void* O, int B, int H, int L, int D, int bq, int bk, hipStream_t stream, float* plan_ms,
         float* attn_ms, bool timed, const Forecast* fc = nullptr, const sparse_attn_plan* plan = nullptr,
-        bool static_scratch = false) {
+        bool static_scratch = false, void* user_ws = nullptr, size_t user_ws_bytes = 0, bool use_user_ws = false) {
   Shape s;
   if (int rc = check_shape(B, H, L, D, bq, bk, true, &s)) return rc;
   if (!Q || !K || !V || !O) return fail(SPARSE_ATTN_ERR_INVALID, "Q, K, V and O must not be NULL");
@@ -1001,15 +1001,29 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
     }
   }
 
+  if (use_user_ws) {
+    const size_t need = workspace_bytes(s);
+    if (!user_ws) return fail(SPARSE_ATTN_ERR_INVALID, "workspace must not be NULL");
+    if ((uintptr_t)user_ws & 255) return fail(SPARSE_ATTN_ERR_INVALID, "workspace must be 256-byte aligned");
+    if (user_ws_bytes < need)
+      return fail(SPARSE_ATTN_ERR_INVALID, "workspace holds %zu bytes, this shape needs %zu (sparse_attn_workspace_bytes)",
+                  user_ws_bytes, need);
+  }
+  if (static_scratch && workspace_bytes(s) > kStaticScratchBytes)
+    return fail(SPARSE_ATTN_ERR_UNSUPPORTED,
+                "this shape needs %zu bytes of scratch, the no-allocation entry point holds %zu "
+                "(B*H*Tq*(ceil(Tkv/32)+3)*4 bytes must fit)", workspace_bytes(s), kStaticScratchBytes);
+
+  int dev = 0, cus = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (plan && dev != plan->dev) return fail(SPARSE_ATTN_ERR_INVALID, "the plan was created on device %d, current device is %d", plan->dev, dev);
+
   PlanBuffers pb;
   if (plan) {
     pb = plan->bufs;
+  } else if (use_user_ws) {
+    pb = carve((char*)user_ws, s);
   } else if (static_scratch) {
-    const size_t need = workspace_bytes(s);
-    if (need > kStaticScratchBytes)
-      return fail(SPARSE_ATTN_ERR_UNSUPPORTED,
-                  "this shape needs %zu bytes of scratch, the no-allocation entry point holds %zu "
-                  "(B*H*Tq*(ceil(Tkv/32)+3)*4 bytes must fit)", need, kStaticScratchBytes);
     void* ws = nullptr;
     if (int rc = static_scratch_ptr(&ws)) return rc;
     pb = carve((char*)ws, s);
@@ -1019,9 +1033,6 @@ int run(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
     pb = carve((char*)ws, s);
   }
 
-  int dev = 0, cus = 0;
-  HIP_TRY(hipGetDevice(&dev));
-  if (plan && dev != plan->dev) return fail(SPARSE_ATTN_ERR_INVALID, "the plan was created on device %d, current device is %d", plan->dev, dev);
   HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
 
   hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
@@ -1174,7 +1185,7 @@ int sparse_attn_plan_create(const uint8_t* cache_flags, const uint8_t* kv_mask, 
   return 0;
 }
 
-int sparse_attn_plan_run(const sparse_attn_plan* plan, const void* Q, const void* K, const void* V, const void* O_cache,
+int sparse_attn_plan_run(sparse_attn_plan* plan, const void* Q, const void* K, const void* V, const void* O_cache,
                          void* O, int D, void* hip_stream) {
   if (!plan) return fail(SPARSE_ATTN_ERR_INVALID, "plan must not be NULL");
   const Shape& s = plan->s;
@@ -1182,7 +1193,7 @@ int sparse_attn_plan_run(const sparse_attn_plan* plan, const void* Q, const void
              nullptr, false, nullptr, plan);
 }
 
-int sparse_attn_plan_run_forecast(const sparse_attn_plan* plan, const void* Q, const void* K, const void* V,
+int sparse_attn_plan_run_forecast(sparse_attn_plan* plan, const void* Q, const void* K, const void* V,
                                   const void* const* O_terms, const float* coef, int n_terms, void* O, int D,
                                   void* hip_stream) {
   if (!plan) return fail(SPARSE_ATTN_ERR_INVALID, "plan must not be NULL");
@@ -1197,6 +1208,31 @@ int sparse_attn_plan_destroy(sparse_attn_plan* plan) {
   const hipError_t e = hipFree(plan->mem);     // waits for work that still uses the buffer
   delete plan;
   if (e != hipSuccess) return fail(SPARSE_ATTN_ERR_HIP, "hipFree failed: %s", hipGetErrorString(e));
+  return 0;
+}
+
+int sparse_attn_fwd_workspace(const void* Q, const void* K, const void* V, const uint8_t* cache_flags,
+                              const uint8_t* kv_mask, const void* O_cache, void* O, int B, int H, int L, int D,
+                              int block_q, int block_k, void* workspace, size_t workspace_size, void* hip_stream) {
+  return run(Q, K, V, cache_flags, kv_mask, O_cache, O, B, H, L, D, block_q, block_k, (hipStream_t)hip_stream, nullptr,
+             nullptr, false, nullptr, nullptr, false, workspace, workspace_size, true);
+}
+
+int sparse_attn_release_scratch(void* hip_stream) {
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_mu);
+    auto it = g_scratch.find(std::make_pair(dev, hip_stream));
+    if (it == g_scratch.end()) return 0;
+    ptr = it->second.ptr;
+    g_scratch.erase(it);
+  }
+  if (ptr) {
+    HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));    // work that still uses the buffer
+    HIP_TRY(hipFree(ptr));
+  }
   return 0;
 }
 

@@ -69,6 +69,18 @@ def test_no_alloc_entry_point_rejects_shapes_beyond_its_scratch():
     assert lib.sparse_attn_fwd_noalloc(None, far[1], far[2], None, None, None, far[3], 1, 1, 128, 128, 128, 128, None) == -1
 
 
+def test_caller_supplied_workspace_is_validated_before_any_device_work():
+    lib = pkg.load_library()
+    far = [ctypes.c_void_p(0x10000 + k * (1 << 40)) for k in range(4)]
+    need = pkg.sparse_attn_workspace_bytes(1, 2, 1024, 128, 128)
+    def call(ws, size):
+        return lib.sparse_attn_fwd_workspace(far[0], far[1], far[2], None, None, None, far[3], 1, 2, 1024, 128, 128, 128,
+                                             ws, size, None)
+    assert call(None, need) == -1 and "workspace" in pkg.sparse_attn_last_error()
+    assert call(ctypes.c_void_p(0x50000040), need) == -1 and "aligned" in pkg.sparse_attn_last_error()
+    assert call(ctypes.c_void_p(0x50000000), need - 1) == -1 and str(need) in pkg.sparse_attn_last_error()
+
+
 def test_workspace_bytes():
     assert pkg.sparse_attn_workspace_bytes(1, 24, 33024, 128, 128) >= 24 * 258 * (4 + 4 + 9 * 4)
     assert pkg.sparse_attn_workspace_bytes(1, 24, 33024, 128, 128) < 1 << 20

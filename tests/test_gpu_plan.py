@@ -116,3 +116,26 @@ def test_plan_without_symbols_is_dense_attention_and_skips_the_prepass_time():
     t_shot = timed(lambda: pkg.sparse_attn_fwd(case.Q, case.K, case.V, None, None, None, O1, 128, 128))
     print(f"[plan] 4608 tokens x 4 heads dense: stored plan {t_plan * 1e3:.1f} us/call, one-shot {t_shot * 1e3:.1f} us/call", flush=True)
     plan.destroy()
+
+
+def test_caller_supplied_workspace_and_scratch_release():
+    """sparse_attn_fwd_workspace writes the bits of the one-shot call using only the caller's buffer (a buffer one
+    byte short is refused); releasing the library's scratch of the stream leaves the next one-shot call working."""
+    w = synth.random_case(synth.BASE_SEED + 97, 2, 3, 1100, 128, 128, 64, keep=0.5, cached_frac=0.3)
+    case = DeviceCase(w)
+    want = case.run()
+    need = pkg.sparse_attn_workspace_bytes(w.B, w.H, w.L, w.block_q, w.block_k)
+    ws = torch.full((need + 512,), 0xAB, dtype=torch.uint8, device=dev())
+    base = (-ws.data_ptr()) % 256
+    O = fresh_O(w)
+    pkg.sparse_attn_fwd_workspace(case.Q, case.K, case.V, case.flags, case.mask, case.Oc, O, w.block_q, w.block_k,
+                                  ws[base:base + need])
+    torch.cuda.synchronize()
+    assert (down_bits(O) == want).all()
+    assert (ws[base + need:] == 0xAB).all() and (ws[:base] == 0xAB).all(), "wrote outside the workspace"
+    with pytest.raises(pkg.SparseAttnError):
+        pkg.sparse_attn_fwd_workspace(case.Q, case.K, case.V, case.flags, case.mask, case.Oc, O, w.block_q, w.block_k,
+                                      ws[base:base + need - 1])
+    pkg.sparse_attn_release_scratch()
+    pkg.sparse_attn_release_scratch()          # nothing left to free: still fine
+    assert (case.run() == want).all()
