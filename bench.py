@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--keep", type=float, default=0.25, help="keep ratio of the headline mask")
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="milliseconds of untimed launches in front of the warm-up steps of every case: the shader clock "
+                         "needs about that long under load to settle after the host-side input set-up (0 = none)")
     ap.add_argument("--no-extras", action="store_true", help="skip the dense run, the sweep and config 4")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-blocks", type=int, default=1280, help="query blocks in the oracle's timed sample")
@@ -104,19 +107,19 @@ def main():
 
     def run_case(M_s, flags, O_cache, steps, warmup, label, settle_ms=0.0):
         """Time `steps` whole-path passes after `warmup` untimed ones; returns per-step (mean and median) and
-        kernel-only times.  settle_ms > 0 keeps launching untimed passes until that much wall time has gone by: the
-        shader clock needs some 100 ms of continuous work to settle after the host-side pause in front of a case,
-        and short kernels measured before that read up to 30 % slow."""
+        kernel-only times.  settle_ms > 0 first keeps launching untimed passes until that much wall time has gone by:
+        the shader clock needs some 100 ms of continuous work to settle after the host-side pause in front of a case
+        (input upload, mask packing), and short kernels measured before that read up to 30 % slow."""
         mask = None if M_s is None else up_u8(pkg.sparse_attn_pack_mask(M_s))
         fl = up_u8(flags)
-        for _ in range(warmup):
-            pkg.sparse_attn_fwd(Q, K, V, fl, mask, O_cache, O, w.block_q, w.block_k)
-        torch.cuda.synchronize()
         t_settle = time.perf_counter()
         while (time.perf_counter() - t_settle) * 1e3 < settle_ms:
             for _ in range(8):
                 pkg.sparse_attn_fwd(Q, K, V, fl, mask, O_cache, O, w.block_q, w.block_k)
             torch.cuda.synchronize()
+        for _ in range(warmup):
+            pkg.sparse_attn_fwd(Q, K, V, fl, mask, O_cache, O, w.block_q, w.block_k)
+        torch.cuda.synchronize()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         pkg.sparse_attn_profile_begin(steps)
         t = time.perf_counter()
@@ -150,9 +153,10 @@ def main():
         log("copy calibration: one 1 GiB device-to-device copy dispatched")
 
     if args.workload == "config4":
-        head = run_case(w.M_s, w.cache_flags, up_bf16(w.O_cache), args.steps, args.warmup, "config 4 (cache + skip, windowed mask)")
+        head = run_case(w.M_s, w.cache_flags, up_bf16(w.O_cache), args.steps, args.warmup, "config 4 (cache + skip, windowed mask)",
+                        args.settle_ms)
     else:
-        head = run_case(w.M_s, None, None, args.steps, args.warmup, f"headline keep={args.keep:g}")
+        head = run_case(w.M_s, None, None, args.steps, args.warmup, f"headline keep={args.keep:g}", args.settle_ms)
 
     extra = {}
     if not args.no_extras:
@@ -161,10 +165,10 @@ def main():
         # Speed-ups compare like with like: every case below, the dense one and a second run of the headline mask
         # included, is taken with the headline's step count, after the same warm-up plus `settle` ms of untimed
         # launches, and the ratios use the MEDIAN step time.
-        settle = 150.0
+        settle = args.settle_ms
         nst = max(args.steps, 10)
         dense = run_case(None, None, None, nst, args.warmup, "dense (same kernel, all pairs kept)", settle)
-        head2 = run_case(w.M_s, None, None, nst, args.warmup, f"headline mask again, settled clocks", settle)
+        head2 = run_case(w.M_s, None, None, nst, args.warmup, "headline mask again", settle)
         speedup = dense["median_ms_per_step"] / head2["median_ms_per_step"]
         extra["dense_ms_per_step"] = dense["median_ms_per_step"]
         extra["dense_tflops"] = flop_per_pair * dense["kept_pairs"] / (dense["median_ms_per_step"] * 1e-3) / 1e12
@@ -173,8 +177,8 @@ def main():
         extra["ideal_speedup"] = 1.0 / head["keep"]
         extra["speedup_over_ideal"] = speedup * head["keep"]
         extra["kernel_only_speedup_vs_dense"] = dense["attn_ms"] / head2["attn_ms"]
-        extra["speedup_method"] = (f"median of {nst} steps per case after {args.warmup} warm-up steps and {settle:.0f} ms of untimed "
-                                   "launches; dense and sparse measured the same way")
+        extra["speedup_method"] = (f"median of {nst} steps per case after {settle:.0f} ms of untimed launches and {args.warmup} "
+                                   "warm-up steps; dense and sparse measured the same way")
         sweep = []
         for keep, skewed in ((0.5, False), (0.125, False), (0.0625, False), (0.5, True), (0.25, True), (0.125, True)):
             rng = np.random.default_rng(np.random.SeedSequence([synth.BASE_SEED + 5, int(round(keep * 10000)), int(skewed)]))
@@ -516,7 +520,8 @@ def main():
                                + (f"band+text+random mask at {head['keep'] * 100:.1f}% keep, no cached blocks"
                                   if args.workload == "sweep" else
                                   f"25% of the video query blocks cached, 3-D window+text+random mask, {head['keep'] * 100:.1f}% of all pairs kept"),
-                   "kept_pairs": head["kept_pairs"], "total_pairs": total_pairs},
+                   "kept_pairs": head["kept_pairs"], "total_pairs": total_pairs,
+                   "settle_ms": args.settle_ms},
         "roofline": {"bound": "mfma", "achieved": head["kernel_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": head["kernel_tflops"] / PEAK_BF16_TFLOPS,
                      "traffic": measured_traffic_bytes(args.keep, H) if args.workload == "sweep" else None},

@@ -60,7 +60,7 @@ extern "C" {
  *   cache_flags  device, uint8 [B,H,Tq] or NULL
  *   kv_mask      device, uint8 [B,H,Tq,ceil(Tkv/8)] or NULL
  *   O_cache      device, bf16 [B,H,L,D]; NULL or equal to O means the cached blocks of O are
- *                already in place (Algorithm 1: "continue if O_i is already updated") and are
+ *                already in place (the early-continue of Algorithm 1's cache branch) and are
  *                not touched
  *   O            device, bf16 [B,H,L,D], written (computed blocks always; cached blocks only
  *                when O_cache is a different tensor).  Must not overlap Q, K or V.
@@ -261,8 +261,8 @@ int sparse_op_reuse(const void* const* terms, const float* coef, int n_terms, vo
 void sparse_taylor_coefficients(int order, float steps, float* coef);
 
 /*
- * Refresh of the stored terms at an Update step.  The paper only says that cached features are forecast from
- * "stored features and their derivatives"; the derivatives are estimated the way the forecasting method it cites
+ * Refresh of the stored terms at an Update step.  Section 3.3 names what the forecast uses (the stored
+ * feature and its derivatives) but not how they are obtained; the derivatives are estimated the way the forecasting method it cites
  * does, by backward finite differences over the Update interval:
  *     new[0] = fresh,   new[d] = (new[d-1] - old[d-1]) / interval  for 1 <= d <= n_valid,   new[d] = 0 beyond
  * with n_valid the number of terms that were valid before this call (0 at the first refresh; the caller then

@@ -1,5 +1,5 @@
-"""CPU oracle of OP_reuse as a Taylor-series forecast (Section 3.3: cached blocks are forecast "via Taylor series
-expansion using stored features and their derivatives"; Section 3.4: the cache-then-reuse path is an element-wise
+"""CPU oracle of OP_reuse as a Taylor-series forecast (Section 3.3: cached blocks are forecast by a Taylor
+expansion around the step at which the feature and its derivatives were stored; Section 3.4: the cache-then-reuse path is an element-wise
 operation of sums and products; Section 3.5: the same operation applied to the cached bias B_c).
 
 TEST INFRASTRUCTURE ONLY.  The operation is the Taylor polynomial written out:

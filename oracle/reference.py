@@ -119,7 +119,7 @@ def sparse_attention(Q, K, V, cache_flags, kv_mask, O_cache, block_q, block_k,
     Returns (O_f64, O_bits).  Computed blocks: fp64 result and its bf16 rounding.
     Cached blocks: O_cache's raw bits (and their widened value).  With O_cache None the
     cached blocks keep whatever O_init_bits holds (zeros if not given) -- the
-    "already updated" case of Algorithm 1.
+    early-continue of the cache branch of Algorithm 1.
     """
     Q, K, V = _u16(Q, "Q"), _u16(K, "K"), _u16(V, "V")
     cache_flags, kv_mask = _u8_or_none(cache_flags), _u8_or_none(kv_mask)

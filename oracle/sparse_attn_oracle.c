@@ -10,7 +10,7 @@
  *   - cache flag set (the paper's F(S_c, i) == 0, "cache-then-reuse" branch of
  *     Algorithm 1 with OP_reuse = identity): the block of O is the block of the cached
  *     output, copied as raw 16-bit patterns.  With no cached tensor the block is left
- *     untouched ("continue if O_i is already updated").
+ *     untouched (the early-continue of that branch).
  *   - otherwise ("compute-on-demand" branch): with J_i the set of key blocks whose
  *     symbol bit J(S_s, i, j) is 1, every row r of the block gets
  *         s_k = <Q_r, K_k> / sqrt(d)          for all keys k in the kept blocks
