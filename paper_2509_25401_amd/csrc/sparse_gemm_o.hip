@@ -28,17 +28,16 @@
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+using sa_gemm::f32x16;
+using sa_gemm::kRowB;
+using sa_gemm::kStepK;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 #define LDS_PTR(T) T __attribute__((address_space(3)))*
 
-constexpr int kStepK = 64;                 // reduction channels per LDS stage
-constexpr int kRowB = kStepK * 2;          // bytes per tile row in LDS
 constexpr int kBN = 128;                   // output channels per workgroup
 constexpr int kMaxTerms = 4;               // stored feature + up to three derivatives
 
@@ -56,8 +55,6 @@ struct GemmOParams {
   int n_terms;           // 0: `addend` is taken as it is
 };
 
-__device__ __forceinline__ int row_swizzle(int row) { return (row >> 1) & 7; }
-
 __device__ __forceinline__ float bf16_bits_to_float(unsigned bits16) {
   return __builtin_bit_cast(float, bits16 << 16);
 }
@@ -68,11 +65,7 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
   constexpr int WN = kBN / 64;             // waves along output channels
   constexpr int NWAVES = WM * WN;
   constexpr int PARTS = D / kStepK;        // stages per head
-  constexpr int W_TILEB = kBN * kRowB;
-  constexpr int X_TILEB = BQ * kRowB;
-  constexpr int W_LOAD = W_TILEB / 1024 / NWAVES;   // direct-to-LDS wave instructions per stage and wave
-  constexpr int X_LOAD = X_TILEB / 1024 / NWAVES;
-  static_assert((W_TILEB / 1024) % NWAVES == 0 && (X_TILEB / 1024) % NWAVES == 0, "stage loads must split evenly");
+  using Stage = sa_gemm::Stages<kBN, BQ, NWAVES>;   // weight rows = the tile's output channels, token rows = the block
 
   // column tile fastest: the 8 XCDs (workgroup n runs on XCD n mod 8) each keep the weight rows of a
   // fixed set of column tiles in their L2 while the token blocks stream past
@@ -108,36 +101,11 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
   // the last token block may be short: loads of missing rows re-read the last row that exists, their results
   // are never stored
   const int rows_valid = min(BQ, p.L - i * BQ);
-  unsigned w_goff[W_LOAD], x_goff[X_LOAD];
-#pragma unroll
-  for (int u = 0; u < W_LOAD; ++u) {
-    const int r = (wave + u * NWAVES) * 8 + lane / 8;
-    w_goff[u] = (unsigned)(r * w_pitch + (((lane % 8) ^ row_swizzle(r)) * 16));
-  }
-#pragma unroll
-  for (int u = 0; u < X_LOAD; ++u) {
-    const int r = (wave + u * NWAVES) * 8 + lane / 8;
-    x_goff[u] = (unsigned)(min(r, rows_valid - 1) * (D * 2) + (((lane % 8) ^ row_swizzle(r)) * 16));
-  }
-  int w_off[kStepK / 16], x_off[kStepK / 16];
-#pragma unroll
-  for (int ks = 0; ks < kStepK / 16; ++ks) {
-    const int o = l32 * kRowB + (((2 * ks + half) ^ row_swizzle(l32)) * 16);
-    w_off[ks] = wn * 64 * kRowB + o;
-    x_off[ks] = 2 * W_TILEB + wm * 64 * kRowB + o;
-  }
-
+  Stage st;
+  st.init(lds_base, wave, lane, wn, wm, w_pitch, (size_t)(D * 2), rows_valid);
   auto issue = [&](int h, int part, auto stage_c) {
-    constexpr int stage = decltype(stage_c)::value;
-    const char* w_src = gW + ((size_t)h * D + (size_t)part * kStepK) * 2;
-    const char* x_src = gO + (size_t)h * p.L * (D * 2) + (size_t)part * kRowB;
-#pragma unroll
-    for (int u = 0; u < W_LOAD; ++u)
-      sa_load_to_lds_16B(w_src, w_goff[u], lds_base + (unsigned)(stage * W_TILEB + (wave + u * NWAVES) * 1024));
-#pragma unroll
-    for (int u = 0; u < X_LOAD; ++u)
-      sa_load_to_lds_16B(x_src, x_goff[u],
-                         lds_base + (unsigned)(2 * W_TILEB + stage * X_TILEB + (wave + u * NWAVES) * 1024));
+    st.template issue<decltype(stage_c)::value>(gW + ((size_t)h * D + (size_t)part * kStepK) * 2,
+                                                gO + (size_t)h * p.L * (D * 2) + (size_t)part * kRowB);
   };
 
   f32x16 acc[2][2];   // [output-channel block][token block] of this wave's 64x64 corner
@@ -148,26 +116,7 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[a][c][e] = 0.f;
 
-  auto compute = [&](auto stage_c) {
-    constexpr int stage = decltype(stage_c)::value;
-    bf16x8 wa[kStepK / 16][2], xb[kStepK / 16][2];
-#pragma unroll
-    for (int ks = 0; ks < kStepK / 16; ++ks) {
-#pragma unroll
-      for (int a = 0; a < 2; ++a) wa[ks][a] = *(const bf16x8*)(smem + stage * W_TILEB + a * 32 * kRowB + w_off[ks]);
-#pragma unroll
-      for (int c = 0; c < 2; ++c) xb[ks][c] = *(const bf16x8*)(smem + stage * X_TILEB + c * 32 * kRowB + x_off[ks]);
-    }
-    __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-    for (int ks = 0; ks < kStepK / 16; ++ks)
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-          acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[ks][a], xb[ks][c], acc[a][c], 0, 0, 0);
-    __builtin_amdgcn_s_setprio(0);
-  };
+  auto compute = [&](auto stage_c) { st.template mfma<decltype(stage_c)::value>(smem, acc); };
 
   // Output side.  The result tile leaves through LDS so that a lane writes 16 contiguous bytes of a
   // token's row (and reads the addend the same way): thread -> (token, group of 8 output channels).
@@ -320,7 +269,7 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
 
 template <int BQ, int D>
 int launch(const GemmOParams& p, int tiles, hipStream_t stream) {
-  constexpr size_t lds = 2 * (size_t)(kBN + BQ) * kRowB;
+  constexpr size_t lds = sa_gemm::Stages<kBN, BQ, (BQ / 64) * (kBN / 64)>::kLdsBytes;
   constexpr int threads = (BQ / 64) * 2 * 64;
   static std::once_flag once;
   static hipError_t attr_err = hipSuccess;

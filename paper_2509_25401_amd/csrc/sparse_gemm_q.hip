@@ -20,15 +20,13 @@
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+using sa_gemm::f32x16;
+using sa_gemm::kRowB;
+using sa_gemm::kStepK;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 
 #define LDS_PTR(T) T __attribute__((address_space(3)))*
-
-constexpr int kStepK = 64;                 // channels per LDS stage
-constexpr int kRowB = kStepK * 2;          // bytes per tile row in LDS
 
 struct GemmQParams {
   const char* X;       // bf16 [B, L, C]
@@ -44,22 +42,13 @@ struct GemmQParams {
   float eps;
 };
 
-// 16-byte chunk permutation of a 128-byte tile row (two rows share a 256-byte bank line)
-__device__ __forceinline__ int row_swizzle(int row) { return (row >> 1) & 7; }
-
 template <int BQ, int D, bool NORM_ROPE>
 __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(const GemmQParams p) {
   constexpr int WM = BQ / 64;              // waves along tokens
   constexpr int WN = D / 64;               // waves along head channels
   constexpr int NWAVES = WM * WN;
-  constexpr int W_TILEB = D * kRowB;       // bytes of one weight stage
-  constexpr int X_TILEB = BQ * kRowB;      // bytes of one token stage
-  constexpr int W_INST = W_TILEB / 1024;   // direct-to-LDS wave instructions per weight stage
-  constexpr int X_INST = X_TILEB / 1024;
-  constexpr int W_LOAD = (W_INST + NWAVES - 1) / NWAVES;
-  constexpr int X_LOAD = (X_INST + NWAVES - 1) / NWAVES;
+  using Stage = sa_gemm::Stages<D, BQ, NWAVES>;   // weight rows = the head's D channels, token rows = the query block
   constexpr int TS = D / 2 + 2;            // padded row of the cos / sin tiles in LDS (floats)
-  static_assert(W_INST % NWAVES == 0 && X_INST % NWAVES == 0, "stage loads must split evenly over the waves");
 
   // tile of this workgroup: head fastest, so the 8 XCDs (workgroup n runs on XCD n mod 8) each keep
   // the weights of a fixed set of heads in their L2
@@ -85,38 +74,10 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
   // are never stored
   const int rows_valid = min(BQ, p.L - i * BQ);
 
-  // per-lane global offsets of this wave's stage loads (8 rows of 128 bytes per instruction)
-  unsigned w_goff[W_LOAD], x_goff[X_LOAD];
-#pragma unroll
-  for (int u = 0; u < W_LOAD; ++u) {
-    const int r = (wave + u * NWAVES) * 8 + lane / 8;
-    w_goff[u] = (unsigned)(r * row_pitch + (((lane % 8) ^ row_swizzle(r)) * 16));
-  }
-#pragma unroll
-  for (int u = 0; u < X_LOAD; ++u) {
-    const int r = (wave + u * NWAVES) * 8 + lane / 8;
-    x_goff[u] = (unsigned)(min(r, rows_valid - 1) * row_pitch + (((lane % 8) ^ row_swizzle(r)) * 16));
-  }
-  // per-lane LDS offsets of the operand reads: row l32 of this wave's first 32-row block, k-step ks
-  int w_off[kStepK / 16], x_off[kStepK / 16];
-#pragma unroll
-  for (int ks = 0; ks < kStepK / 16; ++ks) {
-    const int o = l32 * kRowB + (((2 * ks + half) ^ row_swizzle(l32)) * 16);
-    w_off[ks] = wn * 64 * kRowB + o;
-    x_off[ks] = 2 * W_TILEB + wm * 64 * kRowB + o;
-  }
-
+  Stage st;
+  st.init(lds_base, wave, lane, wn, wm, row_pitch, row_pitch, rows_valid);
   auto issue = [&](int kstep, auto stage_c) {
-    constexpr int stage = decltype(stage_c)::value;
-    const char* w_src = gW + (size_t)kstep * kRowB;
-    const char* x_src = gX + (size_t)kstep * kRowB;
-#pragma unroll
-    for (int u = 0; u < W_LOAD; ++u)
-      sa_load_to_lds_16B(w_src, w_goff[u], lds_base + (unsigned)(stage * W_TILEB + (wave + u * NWAVES) * 1024));
-#pragma unroll
-    for (int u = 0; u < X_LOAD; ++u)
-      sa_load_to_lds_16B(x_src, x_goff[u],
-                         lds_base + (unsigned)(2 * W_TILEB + stage * X_TILEB + (wave + u * NWAVES) * 1024));
+    st.template issue<decltype(stage_c)::value>(gW + (size_t)kstep * kRowB, gX + (size_t)kstep * kRowB);
   };
 
   f32x16 acc[2][2];   // [d block][token block] of this wave's 64x64 corner
@@ -127,29 +88,7 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[a][c][e] = 0.f;
 
-  auto compute = [&](auto stage_c) {
-    // the stage is a compile-time constant: every LDS address is a lane register plus an immediate.
-    // All 16 operand reads of the stage are issued before the first MFMA, which then only waits for
-    // its own two operands.
-    constexpr int stage = decltype(stage_c)::value;
-    bf16x8 wa[kStepK / 16][2], xb[kStepK / 16][2];
-#pragma unroll
-    for (int ks = 0; ks < kStepK / 16; ++ks) {
-#pragma unroll
-      for (int a = 0; a < 2; ++a) wa[ks][a] = *(const bf16x8*)(smem + stage * W_TILEB + a * 32 * kRowB + w_off[ks]);
-#pragma unroll
-      for (int c = 0; c < 2; ++c) xb[ks][c] = *(const bf16x8*)(smem + stage * X_TILEB + c * 32 * kRowB + x_off[ks]);
-    }
-    __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-    for (int ks = 0; ks < kStepK / 16; ++ks)
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-          acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[ks][a], xb[ks][c], acc[a][c], 0, 0, 0);
-    __builtin_amdgcn_s_setprio(0);
-  };
+  auto compute = [&](auto stage_c) { st.template mfma<decltype(stage_c)::value>(smem, acc); };
 
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;
@@ -287,7 +226,7 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
 
 template <int BQ, int D, bool NORM_ROPE>
 int launch(const GemmQParams& p, int tiles, hipStream_t stream) {
-  constexpr size_t stage_lds = 2 * (size_t)(D + BQ) * kRowB;
+  constexpr size_t stage_lds = sa_gemm::Stages<D, BQ, (BQ / 64) * (D / 64)>::kLdsBytes;
   constexpr size_t epi_lds = NORM_ROPE ? (size_t)(2 * BQ * (D / 2 + 2) + 2 * BQ) * 4 : 0;   // cos, sin tiles + row sums
   constexpr size_t lds = stage_lds > epi_lds ? stage_lds : epi_lds;
   constexpr int threads = (BQ / 64) * (D / 64) * 64;
