@@ -160,12 +160,29 @@ def main():
 
     extra = {}
     if not args.no_extras:
-        few = max(3, min(args.steps, 10))
-        warm = 3          # the host-side mask work before each case lets the clocks drop: ramp them up again first
         # Speed-ups compare like with like: every case below, the dense one and a second run of the headline mask
         # included, is taken with the headline's step count, after the same warm-up plus `settle` ms of untimed
         # launches, and the ratios use the MEDIAN step time.
         settle = args.settle_ms
+
+        def time_call(fn, reps=20):
+            """Mean milliseconds per call of `fn` over `reps` back-to-back calls, after the same clock-settling phase
+            as the attention cases (untimed calls for settle_ms, at least three)."""
+            t0, n = time.perf_counter(), 0
+            while n < 3 or (time.perf_counter() - t0) * 1e3 < settle:
+                fn()
+                n += 1
+                if n % 8 == 0:
+                    torch.cuda.synchronize()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
         nst = max(args.steps, 10)
         dense = run_case(None, None, None, nst, args.warmup, "dense (same kernel, all pairs kept)", settle)
         head2 = run_case(w.M_s, None, None, nst, args.warmup, "headline mask again", settle)
@@ -204,14 +221,8 @@ def main():
         # same workload with OP_reuse = first-order Taylor forecast in the cache branch (two stored terms)
         fl4, mk4 = up_u8(w4.cache_flags), up_u8(pkg.sparse_attn_pack_mask(w4.M_s))
         coef = pkg.sparse_taylor_coefficients(1, 2.0)
-        for _ in range(2):
-            pkg.sparse_attn_fwd_forecast(Q, K, V, fl4, mk4, [Oc, V], coef, O, w.block_q, w.block_k)
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        for _ in range(few):
-            pkg.sparse_attn_fwd_forecast(Q, K, V, fl4, mk4, [Oc, V], coef, O, w.block_q, w.block_k)
-        torch.cuda.synchronize()
-        extra["config4"]["ms_per_step_taylor_order1"] = (time.perf_counter() - t) / few * 1e3
+        extra["config4"]["ms_per_step_taylor_order1"] = time_call(
+            lambda: pkg.sparse_attn_fwd_forecast(Q, K, V, fl4, mk4, [Oc, V], coef, O, w.block_q, w.block_k))
         log(f"config4 with first-order forecast in the cache branch: {extra['config4']['ms_per_step_taylor_order1']:.3f} ms/step")
         del fl4, mk4
         Q.copy_(up_bf16(w.Q)); K.copy_(up_bf16(w.K)); V.copy_(up_bf16(w.V))
@@ -228,52 +239,29 @@ def main():
         extra["paper_operating_points"] = pts
         del Oc
     if not args.no_extras:
-        # 2K-image shape (17K tokens: 128 x 128 patches + 512 text tokens), dense and at 25 % keep, through a stored plan
-        L17, T17 = 16896, 132
-        g17 = torch.Generator(device=dev); g17.manual_seed(17)
-        q17, k17, v17 = (torch.randn((1, H, L17, w.D), device=dev, generator=g17).to(torch.bfloat16) for _ in range(3))
-        o17 = torch.empty_like(q17)
-        rng17 = np.random.default_rng(np.random.SeedSequence([synth.BASE_SEED + 17]))
-        M17 = synth.video_sweep_mask(rng17, 1, H, T17, 4, 0.25, False)
-        res17 = {}
-        for label, M in (("dense", None), ("keep25", M17)):
-            mk = None if M is None else up_u8(pkg.sparse_attn_pack_mask(M))
-            plan = pkg.SparseAttnPlan(None, mk, 1, H, L17, w.block_q, w.block_k)
-            for _ in range(warm):
-                plan.run(q17, k17, v17, None, o17)
-            torch.cuda.synchronize()
-            t = time.perf_counter()
-            for _ in range(few):
-                plan.run(q17, k17, v17, None, o17)
-            torch.cuda.synchronize()
-            ms = (time.perf_counter() - t) / few * 1e3
-            kept = H * T17 * T17 if M is None else int(M.sum())
-            res17[label] = dict(ms_per_step=ms, keep=kept / (H * T17 * T17), eff_tflops=flop_per_pair * kept / ms / 1e9)
-            plan.destroy()
-        res17["speedup_vs_dense"] = res17["dense"]["ms_per_step"] / res17["keep25"]["ms_per_step"]
-        extra["image_17k_tokens"] = res17
-        log(f"17K tokens (2K image), stored plan: dense {res17['dense']['ms_per_step']:.3f} ms ({res17['dense']['eff_tflops']:.0f} TFLOP/s), "
-            f"keep {res17['keep25']['keep']:.3f}: {res17['keep25']['ms_per_step']:.3f} ms ({res17['keep25']['eff_tflops']:.0f} TFLOP/s), "
-            f"{res17['speedup_vs_dense']:.2f}x")
-        del q17, k17, v17, o17
-        def time_call(fn, reps=20):
-            """Mean milliseconds per call of `fn` over `reps` back-to-back calls, after the same clock-settling phase
-            as the attention cases (untimed calls for settle_ms, at least three)."""
-            t0, n = time.perf_counter(), 0
-            while n < 3 or (time.perf_counter() - t0) * 1e3 < settle:
-                fn()
-                n += 1
-                if n % 8 == 0:
-                    torch.cuda.synchronize()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                fn()
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / reps
-
+        # the image shapes the paper also benchmarks (4.5K tokens: a 1K image; 17K tokens: a 2K image, 128 x 128 patches
+        # + 512 text tokens), dense and at 25 % keep, through a stored plan
+        for key, Li, seed in (("image_4k_tokens", 4608, 4), ("image_17k_tokens", 16896, 17)):
+            Ti = Li // w.block_q
+            gi = torch.Generator(device=dev); gi.manual_seed(seed)
+            qi, ki, vi = (torch.randn((1, H, Li, w.D), device=dev, generator=gi).to(torch.bfloat16) for _ in range(3))
+            oi = torch.empty_like(qi)
+            rngi = np.random.default_rng(np.random.SeedSequence([synth.BASE_SEED + seed]))
+            Mi = synth.video_sweep_mask(rngi, 1, H, Ti, 4, 0.25, False)
+            resi = {}
+            for label, M in (("dense", None), ("keep25", Mi)):
+                mk = None if M is None else up_u8(pkg.sparse_attn_pack_mask(M))
+                plan = pkg.SparseAttnPlan(None, mk, 1, H, Li, w.block_q, w.block_k)
+                ms = time_call(lambda: plan.run(qi, ki, vi, None, oi), reps=50)
+                kept = H * Ti * Ti if M is None else int(M.sum())
+                resi[label] = dict(ms_per_step=ms, keep=kept / (H * Ti * Ti), eff_tflops=flop_per_pair * kept / ms / 1e9)
+                plan.destroy()
+            resi["speedup_vs_dense"] = resi["dense"]["ms_per_step"] / resi["keep25"]["ms_per_step"]
+            extra[key] = resi
+            log(f"{Li} tokens (image), stored plan: dense {resi['dense']['ms_per_step']:.3f} ms ({resi['dense']['eff_tflops']:.0f} TFLOP/s), "
+                f"keep {resi['keep25']['keep']:.3f}: {resi['keep25']['ms_per_step']:.3f} ms ({resi['keep25']['eff_tflops']:.0f} TFLOP/s), "
+                f"{resi['speedup_vs_dense']:.2f}x")
+            del qi, ki, vi, oi
         # the step before attention (GEMM-Q, Section 3.5): 3072 channels -> 24 heads x 128, flags skip tiles
         C = 3072
         g = torch.Generator(device=dev); g.manual_seed(7)
