@@ -37,6 +37,13 @@ __device__ __forceinline__ const char* sa_uniform_ptr(const char* ptr) {
 
 // s_waitcnt vmcnt(0) only: expcnt and lgkmcnt fields left at their maxima
 __device__ __forceinline__ void sa_wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// s_waitcnt vmcnt(N): at most the N newest vector-memory requests of the wave are still outstanding (loads
+// return in order).  The six-bit count is split over bits 3:0 and 15:14 of the immediate.
+template <int N>
+__device__ __forceinline__ void sa_wait_vmem_but() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a six-bit counter");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 
 // ---------------------------------------------------------------------------------------
 // Operand staging of the two projection kernels (query and output projection).

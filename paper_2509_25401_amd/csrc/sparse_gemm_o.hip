@@ -128,44 +128,7 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
     const int token = it * (NT / 16) + tid / 16;
     return ((out_row0 + token) * p.C_out + col * kBN + out_g * 8) * 2;
   };
-  // the addend (cached bias) is fetched now, so that its latency hides behind the reduction loop
   u32x4 add_bits[OUT_ITERS];
-  if (p.addend) {
-#pragma unroll
-    for (int it = 0; it < OUT_ITERS; ++it)
-      if (it * (NT / 16) + tid / 16 < rows_valid) add_bits[it] = *(const u32x4*)(p.addend + out_offset(it));
-    if (p.n_terms > 0) {
-      // OP_reuse(B_c): fp32 sum of the scaled terms in term order, one rounding to bf16 (what the element-wise
-      // kernel computes), kept packed like a plain addend
-#pragma unroll
-      for (int it = 0; it < OUT_ITERS; ++it) {
-        if (it * (NT / 16) + tid / 16 >= rows_valid) continue;
-        float v[8];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          v[2 * e] = p.coef[0] * bf16_bits_to_float(add_bits[it][e] & 0xffffu);
-          v[2 * e + 1] = p.coef[0] * bf16_bits_to_float(add_bits[it][e] >> 16);
-        }
-        for (int d = 1; d < p.n_terms; ++d) {
-          const u32x4 tb = *(const u32x4*)(p.term[d - 1] + out_offset(it));
-          const float cd = p.coef[d];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            v[2 * e] = fmaf(cd, bf16_bits_to_float(tb[e] & 0xffffu), v[2 * e]);
-            v[2 * e + 1] = fmaf(cd, bf16_bits_to_float(tb[e] >> 16), v[2 * e + 1]);
-          }
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          bf16x2 pr;
-          pr[0] = (__bf16)v[2 * e];
-          pr[1] = (__bf16)v[2 * e + 1];
-          add_bits[it][e] = __builtin_bit_cast(unsigned, pr);
-        }
-      }
-    }
-  }
-
   float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (p.bias) {
 #pragma unroll
@@ -192,8 +155,48 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
     }
     if (it * (NT / 16) + tid / 16 < rows_valid) *(u32x4*)(p.Out + out_offset(it)) = pk;
   };
+  // The addend (cached bias) is requested right after the first stage of the reduction loop: the stage's data comes
+  // from L2 and is needed first, the addend comes from HBM and is needed last, and loads return in order.
+  auto fetch_addend = [&]() {
+    if (p.addend) {
+#pragma unroll
+      for (int it = 0; it < OUT_ITERS; ++it)
+        if (it * (NT / 16) + tid / 16 < rows_valid) add_bits[it] = *(const u32x4*)(p.addend + out_offset(it));
+      if (p.n_terms > 0) {
+        // OP_reuse(B_c): fp32 sum of the scaled terms in term order, one rounding to bf16 (what the element-wise
+        // kernel computes), kept packed like a plain addend
+#pragma unroll
+        for (int it = 0; it < OUT_ITERS; ++it) {
+          if (it * (NT / 16) + tid / 16 >= rows_valid) continue;
+          float v[8];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[2 * e] = p.coef[0] * bf16_bits_to_float(add_bits[it][e] & 0xffffu);
+            v[2 * e + 1] = p.coef[0] * bf16_bits_to_float(add_bits[it][e] >> 16);
+          }
+          for (int d = 1; d < p.n_terms; ++d) {
+            const u32x4 tb = *(const u32x4*)(p.term[d - 1] + out_offset(it));
+            const float cd = p.coef[d];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              v[2 * e] = fmaf(cd, bf16_bits_to_float(tb[e] & 0xffffu), v[2 * e]);
+              v[2 * e + 1] = fmaf(cd, bf16_bits_to_float(tb[e] >> 16), v[2 * e + 1]);
+            }
+          }
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            bf16x2 pr;
+            pr[0] = (__bf16)v[2 * e];
+            pr[1] = (__bf16)v[2 * e + 1];
+            add_bits[it][e] = __builtin_bit_cast(unsigned, pr);
+          }
+        }
+      }
+    }
+  };
   if (heads == 0ull) {
     // no head of this token block is selected: the tile is addend + bias, straight from registers
+    fetch_addend();
 #pragma unroll
     for (int it = 0; it < OUT_ITERS; ++it) {
       float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -216,17 +219,25 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
   };
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;
+  bool first = true;
   auto step = [&](auto cur, auto other) {
     int nh, npart;
     advance(nh, npart);
-    sa_wait_vmem();
+    // stage 0 has landed; the addend's OUT_ITERS requests, issued after it, may still be out.  Only where every
+    // wave has issued all of them: in a short last block a wave skips those of rows that do not exist.
+    if (first && p.addend && p.n_terms == 0 && rows_valid == BQ)
+      sa_wait_vmem_but<OUT_ITERS>();
+    else
+      sa_wait_vmem();
+    first = false;
     __syncthreads();   // this stage has landed for every wave; the other buffer is free
     if (nh >= 0) issue(nh, npart, other);
     compute(cur);
     h = nh;
     part = npart;
   };
-  if (h >= 0) issue(h, 0, S0{});
+  issue(h, 0, S0{});
+  fetch_addend();
   while (h >= 0) {
     step(S0{}, S1{});
     if (h < 0) break;
