@@ -433,6 +433,34 @@ def main():
             f"dense step {dense_ms:.3f} ms, dispatch step {disp_ms:.3f} ms ({dense_ms / disp_ms:.2f}x), interval {interval_ms:.3f} ms "
             f"({N_int * dense_ms / interval_ms:.2f}x over {N_int} dense steps)")
         del Xp, Wq, Wo, Q2, Bc, add, Yo, termsB, rc, rs, ang
+    if not args.no_extras:
+        # the rate of a loop of nothing but the MFMA instruction the kernels run on, on this machine (bench-side probe
+        # library, not the product): constant operands, then random ones -- the clock a power-limited chip holds
+        # under matrix load depends on the data
+        probe_path = os.path.join(ROOT, "bench_mfma_probe.so")
+        if os.path.exists(probe_path):
+            import ctypes
+            probe = ctypes.CDLL(probe_path)
+            probe.bench_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+            probe.bench_mfma_probe.restype = ctypes.c_int
+            res = {}
+            for name, rnd in (("constant_operands", 0), ("random_operands", 1)):
+                tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+                rc = probe.bench_mfma_probe(rnd, 12, ctypes.byref(tf), ctypes.byref(mhz))
+                if rc != 0:
+                    log(f"mfma probe failed with code {rc}")
+                    res = None
+                    break
+                res[name + "_tflops"], res[name + "_mhz"] = tf.value, mhz.value
+            if res:
+                res["attn_kernel_over_random_operand_rate"] = head["kernel_tflops"] / res["random_operands_tflops"]
+                log(f"mfma-only loop: {res['constant_operands_tflops']:.0f} TFLOP/s at {res['constant_operands_mhz']:.0f} MHz on constant operands, "
+                    f"{res['random_operands_tflops']:.0f} TFLOP/s at {res['random_operands_mhz']:.0f} MHz on random ones; "
+                    f"attention kernel = {res['attn_kernel_over_random_operand_rate']:.2f} of the latter")
+            extra["mfma_only"] = res
+        else:
+            log("bench_mfma_probe.so not built: extra.mfma_only left out")
+            extra["mfma_only"] = None
     extra["dense_equiv_tops"] = head["dense_equiv_tops"]
     extra["sparsity"] = 1.0 - head["keep"]
     extra["median_ms_per_step"] = head["median_ms_per_step"]
