@@ -72,7 +72,7 @@ constexpr int kHwRegXccId = (3 << 11) | 20;   // s_getreg operand: 4 bits at off
 constexpr int kOrderThreads = 1024;
 constexpr int kMaxTerms = 4;            // stored feature + up to three derivatives
 constexpr int kMfmaPrio = 1;            // wave priority while it feeds the matrix pipe
-constexpr float kSumLimit = 256.0f;     // a lane's 32 weights of one sub-tile may add up to this before the reference moves
+constexpr float kSumLimit = 256.0f;     // a lane's 16 weights of one 32-key block may add up to this before the reference moves
 
 struct AttnParams {
   const char* Q;
