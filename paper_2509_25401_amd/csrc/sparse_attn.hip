@@ -5,8 +5,9 @@
 //               32-bit words (bit j of the row = key block j, padding cleared), counts the
 //               kept key blocks of every non-cached row and notes the first of them;
 //   plan_order  sorts the rows into one work queue per XCD (a head's rows all go to one XCD, so
-//               its K/V stream through one L2): heaviest rows first (16 kept-count buckets), rows
-//               of one head adjacent inside a bucket, cached rows (plain copies) last;
+//               its K/V stream through one L2): head by head and heaviest rows first inside a
+//               head (63 kept-count buckets), or heaviest rows of all heads first when single
+//               rows are a large part of a workgroup's share; cached rows (plain copies) last;
 //   attn        a persistent grid of two workgroups per CU pulls items from its XCD's queue and
 //               steals from the others when that is drained.  A compute item is one query block:
 //               Q lives in registers as stored (the 1/sqrt(D) scale is applied to the fp32 score),
@@ -57,9 +58,11 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 #define GLOBAL_PTR(T) T __attribute__((address_space(1)))*
 
 constexpr int kKeys = 64;             // keys per LDS sub-tile
-constexpr int kBuckets = 16;          // kept-count buckets of the work ordering
+constexpr int kBuckets = 63;          // kept-count buckets of the work ordering (+ one for cached rows: a lane each)
+constexpr int kCoarseBuckets = 16;    // buckets when the order is longest-first across heads
+constexpr int kWgsPerXcd = 64;        // workgroups of the persistent grid per XCD (32 CUs x 2) the ordering plans for
 constexpr int kXcds = 8;               // accelerator dies (XCDs) of the MI355X, each with its own L2
-constexpr int kMaxHeadGroups = 64;    // head groups per (XCD, bucket) in the ordering histogram
+constexpr int kMaxHeadGroups = 24;    // head groups per (XCD, bucket) in the ordering histogram (48 KiB of LDS)
 constexpr int kMaxTq = 16384;
 constexpr unsigned kCopyFlag = 0x80000000u;
 // Queue counters: every queue head sits in a 128-byte line of its own (all workgroups of an XCD bump the same
@@ -148,17 +151,30 @@ __global__ void reset_queues(const uint32_t* __restrict__ init, uint32_t* __rest
   }
 }
 
-// Work list order: one queue per XCD (head bh belongs to XCD bh % kXcds, so the workgroups of
-// an XCD stream the K/V of one head at a time through that XCD's L2); inside a queue the
-// heaviest rows first (kBuckets kept-count buckets, longest-processing-time-first), rows of one
-// head adjacent inside a bucket, cached rows (plain copies) last.
-__device__ inline int order_major(int key, int Tkv) {
-  // kept count < 2^16 and kBuckets = 16: the product fits in 32 bits
-  return key < 0 ? kBuckets : (kBuckets - 1) - (int)((unsigned)(key & 0xffff) * kBuckets / (unsigned)(Tkv + 1));
+// Work list order: one queue per XCD (head bh belongs to XCD bh % kXcds).  Rows are binned by kept count
+// (kBuckets buckets) and by head (group); cached rows (plain copies) of all heads come at the very end.
+//   head-major   one head after the other, inside a head the heaviest rows first.  All workgroups of an XCD then
+//                stream the K/V of the same head at the same time, and because rows that run at the same time have
+//                (almost) the same number of kept blocks they also stay at about the same key position while they
+//                sweep it: a tile one of them has fetched is still in that XCD's L2 when the others ask for it.
+//                What counts for the balance is the end of the queue, and there the light rows of the last head
+//                come last -- as long as no single row is a large part of a workgroup's whole share.
+//   otherwise    heaviest rows of all heads first (longest-processing-time-first over the whole queue), rows of one
+//                head adjacent inside a bucket.  Taken when the heaviest row of the queue is more than a third of
+//                what one workgroup gets to do in total: the heavy rows of the last head would start too late.
+// Kept-count bucket of a row, heaviest = 0: kBuckets fine buckets in head-major order (rows that run side by side
+// should be of nearly the same length), kCoarseBuckets otherwise; cached rows always get bucket kBuckets.
+__device__ inline int order_major(int key, int Tkv, int head_major) {
+  const int nb = head_major ? kBuckets : kCoarseBuckets;
+  // kept count < 2^16 and nb < 2^6: the product fits in 32 bits
+  return key < 0 ? kBuckets : (nb - 1) - (int)((unsigned)(key & 0xffff) * nb / (unsigned)(Tkv + 1));
 }
-__device__ inline int order_bin(int key, int row, int Tq, int Tkv, int shift, int groups) {
+__device__ inline int order_bin(int key, int row, int Tq, int Tkv, int shift, int groups, const int* head_major) {
   const int bh = row / Tq;
-  return ((bh % kXcds) * (kBuckets + 1) + order_major(key, Tkv)) * groups + ((bh / kXcds) >> shift);
+  const int xcd = bh % kXcds;
+  const int group = (bh / kXcds) >> shift, major = order_major(key, Tkv, head_major[xcd]);
+  const int inner = (major == kBuckets || !head_major[xcd]) ? major * groups + group : group * kBuckets + major;
+  return xcd * (kBuckets + 1) * groups + inner;
 }
 
 __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __restrict__ keys, int N, int Tq,
@@ -167,12 +183,45 @@ __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __res
                                                             uint32_t* __restrict__ queues) {
   __shared__ uint32_t bins[kXcds * (kBuckets + 1) * kMaxHeadGroups];
   __shared__ uint32_t partial[kOrderThreads];
+  __shared__ unsigned long long queue_kept[kXcds];   // kept key blocks of all rows of a queue
+  __shared__ uint32_t queue_heaviest[kXcds];         // ... of its heaviest row
+  __shared__ int head_major[kXcds];
   const int tid = threadIdx.x;
   const int per_xcd = (kBuckets + 1) * groups;
   const int nbins = kXcds * per_xcd;
   for (int b = tid; b < nbins; b += kOrderThreads) bins[b] = 0;
+  if (tid < kXcds) {
+    queue_kept[tid] = 0ull;
+    queue_heaviest[tid] = 0u;
+  }
   __syncthreads();
-  for (int r = tid; r < N; r += kOrderThreads) atomicAdd(&bins[order_bin(keys[r], r, Tq, Tkv, shift, groups)], 1u);
+  {
+    // one wave per head: sum and maximum of the kept counts of its rows (a head has at most 2^14 rows of at most
+    // 2^16 - 1 kept blocks: the sum fits in 32 bits), one atomic per head
+    const int wave = tid >> 6, lane = tid & 63;
+    for (int bh = wave; bh < N / Tq; bh += kOrderThreads / 64) {
+      uint32_t sum = 0, heaviest = 0;
+      for (int i = lane; i < Tq; i += 64) {
+        const int key = keys[bh * Tq + i];
+        if (key >= 0) {
+          sum += (uint32_t)(key & 0xffff);
+          heaviest = max(heaviest, (uint32_t)(key & 0xffff));
+        }
+      }
+      for (int off = 32; off > 0; off >>= 1) {
+        sum += __shfl_xor(sum, off);
+        heaviest = max(heaviest, __shfl_xor(heaviest, off));
+      }
+      if (lane == 0) {
+        atomicAdd(&queue_kept[bh % kXcds], (unsigned long long)sum);
+        atomicMax(&queue_heaviest[bh % kXcds], heaviest);
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < kXcds) head_major[tid] = 3ull * kWgsPerXcd * queue_heaviest[tid] <= queue_kept[tid] ? 1 : 0;
+  __syncthreads();
+  for (int r = tid; r < N; r += kOrderThreads) atomicAdd(&bins[order_bin(keys[r], r, Tq, Tkv, shift, groups, head_major)], 1u);
   __syncthreads();
   // exclusive scan of bins: contiguous chunk per thread, then a scan over the chunk sums
   const int chunk = (nbins + kOrderThreads - 1) / kOrderThreads;
@@ -217,7 +266,7 @@ __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __res
         const bool valid = i < Tq;
         const int r = bh * Tq + min(i, Tq - 1);
         const int key = keys[r];
-        const int major = valid ? order_major(key, Tkv) : -1;
+        const int major = valid ? order_major(key, Tkv, head_major[bh % kXcds]) : -1;
         unsigned long long todo = __ballot(valid);
         uint32_t rank = 0;
         while (todo != 0ull) {
@@ -229,7 +278,7 @@ __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __res
           todo &= ~same;
         }
         if (valid) {
-          const uint32_t pos = bins[order_bin(key, r, Tq, Tkv, shift, groups)] + rank;
+          const uint32_t pos = bins[order_bin(key, r, Tq, Tkv, shift, groups, head_major)] + rank;
           order[2 * pos] = (uint32_t)r | (key < 0 ? kCopyFlag : 0u);
           order[2 * pos + 1] = (uint32_t)key;
         }
@@ -239,7 +288,7 @@ __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __res
   }
   for (int r = tid; r < N; r += kOrderThreads) {
     const int key = keys[r];
-    const uint32_t pos = atomicAdd(&bins[order_bin(key, r, Tq, Tkv, shift, groups)], 1u);
+    const uint32_t pos = atomicAdd(&bins[order_bin(key, r, Tq, Tkv, shift, groups, head_major)], 1u);
     order[2 * pos] = (uint32_t)r | (key < 0 ? kCopyFlag : 0u);
     order[2 * pos + 1] = (uint32_t)key;
   }
