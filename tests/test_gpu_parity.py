@@ -277,8 +277,8 @@ def test_score_ranges_that_force_the_exponent_reference_to_move(profile):
 
 
 def test_more_heads_than_the_order_pass_has_bins():
-    """640 (batch, head) pairs: 80 per XCD queue, more than the 64 head groups of the ordering pass, so heads are
-    grouped in pairs there; every block must still be computed exactly once."""
+    """640 (batch, head) pairs: 80 per XCD queue, more than the 24 head groups of the ordering pass, so heads are
+    grouped in fours there; every block must still be computed exactly once."""
     w = synth.random_case(synth.BASE_SEED + 310, 8, 80, 256, 64, 128, 64, keep=0.6, cached_frac=0.25)
     got = DeviceCase(w).run()
     ref, ref_bits = oracle_full(w)
