@@ -5,9 +5,9 @@
 //               32-bit words (bit j of the row = key block j, padding cleared), counts the
 //               kept key blocks of every non-cached row and notes the first of them;
 //   plan_order  sorts the rows into one work queue per XCD (a head's rows all go to one XCD, so
-//               its K/V stream through one L2): head by head and heaviest rows first inside a
-//               head (63 kept-count buckets), or heaviest rows of all heads first when single
-//               rows are a large part of a workgroup's share; cached rows (plain copies) last;
+//               its K/V stream through one L2): rows that are a large part of a workgroup's
+//               share first (longest first), the others head by head and heaviest first inside a
+//               head (55 kept-count buckets), cached rows (plain copies) last;
 //   attn        a persistent grid of two workgroups per CU pulls items from its XCD's queue and
 //               steals from the others when that is drained.  A compute item is one query block:
 //               Q lives in registers as stored (the 1/sqrt(D) scale is applied to the fp32 score),
@@ -58,8 +58,9 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 #define GLOBAL_PTR(T) T __attribute__((address_space(1)))*
 
 constexpr int kKeys = 64;             // keys per LDS sub-tile
-constexpr int kBuckets = 63;          // kept-count buckets of the work ordering (+ one for cached rows: a lane each)
-constexpr int kCoarseBuckets = 16;    // buckets when the order is longest-first across heads
+constexpr int kLongBuckets = 8;       // kept-count buckets of the long rows of a queue (longest first, across heads)
+constexpr int kFineBuckets = 55;      // ... of its other rows (head by head); with the bucket of cached rows: 64,
+constexpr int kCachedBucket = kLongBuckets + kFineBuckets;   // one lane each in the ranking pass
 constexpr int kWgsPerXcd = 64;        // workgroups of the persistent grid per XCD (32 CUs x 2) the ordering plans for
 constexpr int kXcds = 8;               // accelerator dies (XCDs) of the MI355X, each with its own L2
 constexpr int kMaxHeadGroups = 24;    // head groups per (XCD, bucket) in the ordering histogram (48 KiB of LDS)
@@ -151,77 +152,102 @@ __global__ void reset_queues(const uint32_t* __restrict__ init, uint32_t* __rest
   }
 }
 
-// Work list order: one queue per XCD (head bh belongs to XCD bh % kXcds).  Rows are binned by kept count
-// (kBuckets buckets) and by head (group); cached rows (plain copies) of all heads come at the very end.
-//   head-major   one head after the other, inside a head the heaviest rows first.  All workgroups of an XCD then
-//                stream the K/V of the same head at the same time, and because rows that run at the same time have
-//                (almost) the same number of kept blocks they also stay at about the same key position while they
-//                sweep it: a tile one of them has fetched is still in that XCD's L2 when the others ask for it.
-//                What counts for the balance is the end of the queue, and there the light rows of the last head
-//                come last -- as long as no single row is a large part of a workgroup's whole share.
-//   otherwise    heaviest rows of all heads first (longest-processing-time-first over the whole queue), rows of one
-//                head adjacent inside a bucket.  Taken when the heaviest row of the queue is more than a third of
-//                what one workgroup gets to do in total: the heavy rows of the last head would start too late.
-// Kept-count bucket of a row, heaviest = 0: kBuckets fine buckets in head-major order (rows that run side by side
-// should be of nearly the same length), kCoarseBuckets otherwise; cached rows always get bucket kBuckets.
-__device__ inline int order_major(int key, int Tkv, int head_major) {
-  const int nb = head_major ? kBuckets : kCoarseBuckets;
-  // kept count < 2^16 and nb < 2^6: the product fits in 32 bits
-  return key < 0 ? kBuckets : (nb - 1) - (int)((unsigned)(key & 0xffff) * nb / (unsigned)(Tkv + 1));
+// Work list order: one queue per XCD (head bh belongs to XCD bh % kXcds), in three parts.
+//   long rows    rows with more kept blocks than `limit` = a third of what one workgroup gets to do in total
+//                (kept blocks of the queue / (3 * kWgsPerXcd)): longest first across heads (kLongBuckets buckets,
+//                heads adjacent inside a bucket), so that none of them starts late.  Uniform masks have none; with
+//                few rows per workgroup (short sequences) every row is long.
+//   other rows   head by head, inside a head the heaviest first (kFineBuckets buckets), inside a bucket in sequence
+//                order.  All workgroups of an XCD then stream the K/V of the same head at the same time, and because
+//                rows that run at the same time have (almost) the same number of kept blocks they also stay at
+//                about the same key position while they sweep it: a tile one of them has fetched is still in that
+//                XCD's L2 when the others ask for it.  What counts for the balance is the end of the queue, and
+//                there the light rows of the last head come last.
+//   cached rows  (plain copies) of all heads at the very end.
+// Bucket of a row: 0 .. kLongBuckets-1 long (heaviest = 0), then kFineBuckets buckets, then kCachedBucket.
+// `lightest` = the smallest kept count among the queue's computed rows: the fine buckets span lightest .. limit, so
+// that masks whose rows differ by a few blocks only are still sorted block by block.
+__device__ inline int order_major(int key, int Tkv, int limit, int lightest) {
+  if (key < 0) return kCachedBucket;
+  const int count = key & 0xffff;   // < 2^16, bucket counts < 2^6: the products fit in 32 bits
+  if (count > limit)
+    return (kLongBuckets - 1) - (int)((unsigned)(count - limit - 1) * kLongBuckets / (unsigned)(Tkv - limit));
+  return kLongBuckets + (kFineBuckets - 1) -
+         (int)((unsigned)(count - lightest) * kFineBuckets / (unsigned)(limit - lightest + 1));
 }
-__device__ inline int order_bin(int key, int row, int Tq, int Tkv, int shift, int groups, const int* head_major) {
+__device__ inline int order_bin(int key, int row, int Tq, int Tkv, int shift, int groups, const int* limit,
+                                const int* lightest) {
   const int bh = row / Tq;
   const int xcd = bh % kXcds;
-  const int group = (bh / kXcds) >> shift, major = order_major(key, Tkv, head_major[xcd]);
-  const int inner = (major == kBuckets || !head_major[xcd]) ? major * groups + group : group * kBuckets + major;
-  return xcd * (kBuckets + 1) * groups + inner;
+  const int group = (bh / kXcds) >> shift, major = order_major(key, Tkv, limit[xcd], lightest[xcd]);
+  int inner;
+  if (major < kLongBuckets)
+    inner = major * groups + group;
+  else if (major < kCachedBucket)
+    inner = kLongBuckets * groups + group * kFineBuckets + (major - kLongBuckets);
+  else
+    inner = kCachedBucket * groups + group;
+  return xcd * (kCachedBucket + 1) * groups + inner;
 }
 
 __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __restrict__ keys, int N, int Tq,
                                                             int Tkv, int shift, int groups,
                                                             uint32_t* __restrict__ order,
                                                             uint32_t* __restrict__ queues) {
-  __shared__ uint32_t bins[kXcds * (kBuckets + 1) * kMaxHeadGroups];
+  __shared__ uint32_t bins[kXcds * (kCachedBucket + 1) * kMaxHeadGroups];
   __shared__ uint32_t partial[kOrderThreads];
   __shared__ unsigned long long queue_kept[kXcds];   // kept key blocks of all rows of a queue
-  __shared__ uint32_t queue_heaviest[kXcds];         // ... of its heaviest row
-  __shared__ int head_major[kXcds];
+  __shared__ int limit[kXcds];                       // kept blocks from which a row of the queue counts as long
+  __shared__ uint32_t heaviest[kXcds], lightest_u[kXcds];   // largest / smallest kept count of its computed rows
+  __shared__ int lightest[kXcds];
+  __shared__ uint32_t seen_rows[kOrderThreads / 64][64];
   const int tid = threadIdx.x;
-  const int per_xcd = (kBuckets + 1) * groups;
+  const int per_xcd = (kCachedBucket + 1) * groups;
   const int nbins = kXcds * per_xcd;
   for (int b = tid; b < nbins; b += kOrderThreads) bins[b] = 0;
   if (tid < kXcds) {
     queue_kept[tid] = 0ull;
-    queue_heaviest[tid] = 0u;
+    heaviest[tid] = 0u;
+    lightest_u[tid] = 0xffffu;
   }
   __syncthreads();
   {
-    // one wave per head: sum and maximum of the kept counts of its rows (a head has at most 2^14 rows of at most
-    // 2^16 - 1 kept blocks: the sum fits in 32 bits), one atomic per head
+    // one wave per head: sum, maximum and minimum of the kept counts of its rows (a head has at most 2^14 rows of at
+    // most 2^16 - 1 kept blocks: the sum fits in 32 bits), one atomic each per head
     const int wave = tid >> 6, lane = tid & 63;
     for (int bh = wave; bh < N / Tq; bh += kOrderThreads / 64) {
-      uint32_t sum = 0, heaviest = 0;
+      uint32_t sum = 0, hi = 0, lo = 0xffffu;
       for (int i = lane; i < Tq; i += 64) {
         const int key = keys[bh * Tq + i];
         if (key >= 0) {
-          sum += (uint32_t)(key & 0xffff);
-          heaviest = max(heaviest, (uint32_t)(key & 0xffff));
+          const uint32_t count = (uint32_t)(key & 0xffff);
+          sum += count;
+          hi = max(hi, count);
+          lo = min(lo, count);
         }
       }
       for (int off = 32; off > 0; off >>= 1) {
         sum += __shfl_xor(sum, off);
-        heaviest = max(heaviest, __shfl_xor(heaviest, off));
+        hi = max(hi, __shfl_xor(hi, off));
+        lo = min(lo, __shfl_xor(lo, off));
       }
       if (lane == 0) {
         atomicAdd(&queue_kept[bh % kXcds], (unsigned long long)sum);
-        atomicMax(&queue_heaviest[bh % kXcds], heaviest);
+        atomicMax(&heaviest[bh % kXcds], hi);
+        atomicMin(&lightest_u[bh % kXcds], lo);
       }
     }
   }
   __syncthreads();
-  if (tid < kXcds) head_major[tid] = 3ull * kWgsPerXcd * queue_heaviest[tid] <= queue_kept[tid] ? 1 : 0;
+  if (tid < kXcds) {
+    // long = more than a third of a workgroup's share; where no row is that long the fine buckets end at the
+    // heaviest row instead
+    const int share = (int)min(queue_kept[tid] / (3ull * kWgsPerXcd), (unsigned long long)Tkv);
+    limit[tid] = (int)heaviest[tid] <= share ? (int)heaviest[tid] : share;
+    lightest[tid] = min((int)lightest_u[tid], limit[tid]);
+  }
   __syncthreads();
-  for (int r = tid; r < N; r += kOrderThreads) atomicAdd(&bins[order_bin(keys[r], r, Tq, Tkv, shift, groups, head_major)], 1u);
+  for (int r = tid; r < N; r += kOrderThreads) atomicAdd(&bins[order_bin(keys[r], r, Tq, Tkv, shift, groups, limit, lightest)], 1u);
   __syncthreads();
   // exclusive scan of bins: contiguous chunk per thread, then a scan over the chunk sums
   const int chunk = (nbins + kOrderThreads - 1) / kOrderThreads;
@@ -253,32 +279,35 @@ __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __res
   // Inside a bin the rows keep their order in the sequence: neighbouring query blocks, which with windowed symbols
   // keep nearly the same key blocks, are then worked on at the same time and find each other's tiles in L2.  A bin
   // holds rows of one head as long as there are no more than kMaxHeadGroups heads per queue: a wave then walks a
-  // head 64 query blocks at a time, lane b counts the rows seen so far in bucket b, and a row's place is the start
-  // of its bin + that count + the rows of its bucket at lower lanes (ballots).  With more heads several of them
+  // head 64 query blocks at a time, keeps the number of rows seen so far in every bucket, and a row's place is the
+  // start of its bin + that count + the rows of its bucket at lower lanes (ballots).  With more heads several of them
   // share a bin and the rows take their places in arrival order.
   if (shift == 0) {
     const int wave = tid >> 6, lane = tid & 63;
     const int heads = N / Tq;
+    volatile uint32_t* seen = seen_rows[wave];   // rows of the current head met so far, per bucket
     for (int bh = wave; bh < heads; bh += kOrderThreads / 64) {
-      uint32_t seen = 0;                                   // lane b: rows of this head in bucket b so far
+      seen[lane] = 0u;
       for (int i0 = 0; i0 < Tq; i0 += 64) {
         const int i = i0 + lane;
         const bool valid = i < Tq;
         const int r = bh * Tq + min(i, Tq - 1);
         const int key = keys[r];
-        const int major = valid ? order_major(key, Tkv, head_major[bh % kXcds]) : -1;
-        unsigned long long todo = __ballot(valid);
-        uint32_t rank = 0;
-        while (todo != 0ull) {
-          const int cur = __shfl(major, (int)__builtin_ctzll(todo));
-          const unsigned long long same = __ballot(major == cur);
-          const uint32_t before = __shfl(seen, cur);
-          if (major == cur) rank = before + (uint32_t)__popcll(same & ((1ull << lane) - 1ull));
-          if (lane == cur) seen += (uint32_t)__popcll(same);
-          todo &= ~same;
+        const int major = valid ? order_major(key, Tkv, limit[bh % kXcds], lightest[bh % kXcds]) : 0;
+        // the lanes whose row falls into the same bucket as this lane's: one ballot per bit of the bucket number
+        unsigned long long same = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 6; ++b) {
+          const unsigned long long set = __ballot((major >> b) & 1);
+          same &= ((major >> b) & 1) ? set : ~set;
         }
         if (valid) {
-          const uint32_t pos = bins[order_bin(key, r, Tq, Tkv, shift, groups, head_major)] + rank;
+          // LDS accesses of a wave execute in program order: every lane reads its bucket's count before the first
+          // lane of each bucket moves it on
+          const uint32_t before = seen[major];
+          const uint32_t rank = before + (uint32_t)__popcll(same & ((1ull << lane) - 1ull));
+          if ((same & ((1ull << lane) - 1ull)) == 0ull) seen[major] = before + (uint32_t)__popcll(same);
+          const uint32_t pos = bins[order_bin(key, r, Tq, Tkv, shift, groups, limit, lightest)] + rank;
           order[2 * pos] = (uint32_t)r | (key < 0 ? kCopyFlag : 0u);
           order[2 * pos + 1] = (uint32_t)key;
         }
@@ -288,7 +317,7 @@ __global__ void __launch_bounds__(kOrderThreads) plan_order(const int32_t* __res
   }
   for (int r = tid; r < N; r += kOrderThreads) {
     const int key = keys[r];
-    const uint32_t pos = atomicAdd(&bins[order_bin(key, r, Tq, Tkv, shift, groups, head_major)], 1u);
+    const uint32_t pos = atomicAdd(&bins[order_bin(key, r, Tq, Tkv, shift, groups, limit, lightest)], 1u);
     order[2 * pos] = (uint32_t)r | (key < 0 ? kCopyFlag : 0u);
     order[2 * pos + 1] = (uint32_t)key;
   }
