@@ -153,7 +153,8 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
       pr[1] = (__bf16)v[2 * e + 1];
       pk[e] = __builtin_bit_cast(unsigned, pr);
     }
-    if (it * (NT / 16) + tid / 16 < rows_valid) *(u32x4*)(p.Out + out_offset(it)) = pk;
+    // streamed once: non-temporal, so that it does not push the weight rows out of the XCD's L2
+    if (it * (NT / 16) + tid / 16 < rows_valid) __builtin_nontemporal_store(pk, (u32x4*)(p.Out + out_offset(it)));
   };
   // The addend (cached bias) is requested right after the first stage of the reduction loop: the stage's data comes
   // from L2 and is needed first, the addend comes from HBM and is needed last, and loads return in order.
@@ -161,7 +162,8 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
     if (p.addend) {
 #pragma unroll
       for (int it = 0; it < OUT_ITERS; ++it)
-        if (it * (NT / 16) + tid / 16 < rows_valid) add_bits[it] = *(const u32x4*)(p.addend + out_offset(it));
+        if (it * (NT / 16) + tid / 16 < rows_valid)
+          add_bits[it] = __builtin_nontemporal_load((const u32x4*)(p.addend + out_offset(it)));
       if (p.n_terms > 0) {
         // OP_reuse(B_c): fp32 sum of the scaled terms in term order, one rounding to bf16 (what the element-wise
         // kernel computes), kept packed like a plain addend
@@ -175,7 +177,7 @@ __global__ void __launch_bounds__((BQ / 64) * 2 * 64, 2) gemm_o_kernel(const Gem
             v[2 * e + 1] = p.coef[0] * bf16_bits_to_float(add_bits[it][e] >> 16);
           }
           for (int d = 1; d < p.n_terms; ++d) {
-            const u32x4 tb = *(const u32x4*)(p.term[d - 1] + out_offset(it));
+            const u32x4 tb = __builtin_nontemporal_load((const u32x4*)(p.term[d - 1] + out_offset(it)));
             const float cd = p.coef[d];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {

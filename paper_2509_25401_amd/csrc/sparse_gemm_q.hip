@@ -25,6 +25,7 @@ using sa_gemm::kRowB;
 using sa_gemm::kStepK;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 #define LDS_PTR(T) T __attribute__((address_space(3)))*
 
@@ -113,7 +114,6 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
 
   // epilogue: lane holds token l32 (+32*c) and, per accumulator quad q4, head channels
   // 32*a + 8*q4 + 4*half + 0..3 of this wave's corner
-  char* qrow0 = p.Q + (((size_t)b * p.H + h) * p.L + (size_t)i * BQ + wm * 64 + l32) * (size_t)(D * 2);
   float inv_rms[2] = {1.f, 1.f};
   if constexpr (NORM_ROPE) {
     // Equation 2: token-wise RMS normalisation over the head's D channels, then the rotation.  The bias
@@ -211,17 +211,45 @@ __global__ void __launch_bounds__((BQ / 64) * (D / 64) * 64, 2) gemm_q_kernel(co
             y[0] = y0; y[1] = y1; y[2] = y2; y[3] = y3;
           }
         }
+        // the finished values go back into the accumulator registers; they leave through LDS below
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[a][c][4 * q4 + e] = y[e];
+      }
+    }
+  // Output side.  A lane holds 4 channels of one token: written from here a store would be 8 bytes per lane, 256
+  // bytes apart.  The tile goes through LDS instead (rows of D bf16, 16-byte chunks XOR-permuted by the token so that
+  // the 32 tokens of a write hit different banks) and leaves as whole rows, 16 bytes per lane, with non-temporal
+  // stores: the projection writes its result once and must not push the weights and token rows out of L2 with it.
+  constexpr int ROWB_OUT = D * 2;            // bytes per token row of the tile
+  constexpr int CH = ROWB_OUT / 16;          // 16-byte chunks per row
+  __syncthreads();                           // every wave is done with the operand stages / the tables
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const int d0 = wn * 64 + 32 * a + 8 * q4 + 4 * half;
+        const int token = wm * 64 + 32 * c + l32;
         bf16x2 lo, hi;
-        lo[0] = (__bf16)y[0];
-        lo[1] = (__bf16)y[1];
-        hi[0] = (__bf16)y[2];
-        hi[1] = (__bf16)y[3];
+        lo[0] = (__bf16)acc[a][c][4 * q4 + 0];
+        lo[1] = (__bf16)acc[a][c][4 * q4 + 1];
+        hi[0] = (__bf16)acc[a][c][4 * q4 + 2];
+        hi[1] = (__bf16)acc[a][c][4 * q4 + 3];
         u32x2 pk;
         pk[0] = __builtin_bit_cast(unsigned, lo);
         pk[1] = __builtin_bit_cast(unsigned, hi);
-        if (wm * 64 + 32 * c + l32 < rows_valid) *(u32x2*)(qrow0 + (size_t)c * 32 * (D * 2) + d0 * 2) = pk;
+        *(u32x2*)(smem + token * ROWB_OUT + (((d0 / 8) ^ (token & (CH - 1))) * 16) + (d0 % 8) * 2) = pk;
       }
-    }
+  __syncthreads();
+  constexpr int NT = NWAVES * 64;
+  char* const out0 = p.Q + (((size_t)b * p.H + h) * p.L + (size_t)i * BQ) * (size_t)ROWB_OUT;
+#pragma unroll
+  for (int it = 0; it < BQ * CH / NT; ++it) {
+    const int token = it * (NT / CH) + tid / CH, ch = tid % CH;
+    const u32x4 v = *(const u32x4*)(smem + token * ROWB_OUT + ((ch ^ (token & (CH - 1))) * 16));
+    if (token < rows_valid) __builtin_nontemporal_store(v, (u32x4*)(out0 + (size_t)token * ROWB_OUT + ch * 16));
+  }
 }
 
 template <int BQ, int D, bool NORM_ROPE>
