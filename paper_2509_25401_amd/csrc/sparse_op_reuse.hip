@@ -28,7 +28,7 @@ __global__ void __launch_bounds__(256) op_reuse_kernel(const ReuseParams p) {
   for (size_t t = (size_t)blockIdx.x * 256 + threadIdx.x; t < p.n_vec; t += stride) {
     bf16x8 v[N];
 #pragma unroll
-    for (int d = 0; d < N; ++d) v[d] = p.term[d][t];
+    for (int d = 0; d < N; ++d) v[d] = __builtin_nontemporal_load(p.term[d] + t);   // streamed once
     bf16x8 r;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -37,7 +37,7 @@ __global__ void __launch_bounds__(256) op_reuse_kernel(const ReuseParams p) {
       for (int d = 1; d < N; ++d) acc = fmaf(p.coef[d], (float)v[d][e], acc);
       r[e] = (__bf16)acc;
     }
-    p.out[t] = r;
+    __builtin_nontemporal_store(r, p.out + t);
   }
 }
 

@@ -104,8 +104,9 @@ __global__ void __launch_bounds__(256) pool_blocks(const uint16_t* __restrict__ 
   const int c = threadIdx.x % TPR, r0 = threadIdx.x / TPR;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int r = r0; r < rows; r += RPP) {
-    const uint4 v = *(const uint4*)(src + (size_t)r * D + c * 8);
-    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+    const u32x4 v = __builtin_nontemporal_load((const u32x4*)(src + (size_t)r * D + c * 8));   // read once
+    const unsigned w[4] = {v[0], v[1], v[2], v[3]};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       acc[2 * e] += __uint_as_float(w[e] << 16);
