@@ -77,6 +77,20 @@ def test_config5_video_sweep_full_size(video_tensors, keep, skewed, nblocks):
     _compare_sample(w, got, _sample_items(w, nblocks, 5), f"config5 keep={keep} skewed={skewed}")
 
 
+def test_text_rows_keep_everything_full_size(video_tensors):
+    """12.5 % keep with the two text query blocks of every head keeping all 258 key blocks: a few rows that are
+    many times longer than the rest (the work list puts such rows in front of the head-by-head part).  The sample
+    holds the heaviest rows (the text rows), the lightest, the median ones and random others."""
+    print("[case] video sweep keep=0.125, text rows dense", flush=True)
+    base = video_tensors
+    w = synth.config_video_sweep(0.125, False, tensors=(base.Q, base.K, base.V))
+    w.M_s[:, :, :2, :] = 1
+    got = DeviceCase(w).run()
+    items = _sample_items(w, 48, 7)
+    assert {0, 1} <= set(items.tolist())
+    _compare_sample(w, got, items, "keep=0.125 + dense text rows")
+
+
 @pytest.mark.parametrize("name", synth.PAPER_POINTS)
 def test_paper_operating_points_full_size(video_tensors, name):
     """The three points the benchmark quotes next to the paper's figures (80 % skipping, 80 % caching, 90 %
