@@ -35,6 +35,21 @@ def test_library_exports_every_declared_symbol():
     assert pkg.sparse_attn_version() >= 100
 
 
+def test_bench_probe_is_a_library_of_its_own():
+    """The MFMA-only probe bench.py reports is built beside it and is neither exported by the product library nor
+    declared in include/; its argument check needs no GPU."""
+    path = os.path.join(ROOT, "bench_mfma_probe.so")
+    if not os.path.exists(path):
+        pytest.skip("bench_mfma_probe.so not built (python -c 'import __graft_entry__ as g; g.build()')")
+    probe = ctypes.CDLL(path)
+    probe.bench_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    probe.bench_mfma_probe.restype = ctypes.c_int
+    assert probe.bench_mfma_probe(0, 0, None, None) == -1          # launches out of range, no result pointer
+    assert probe.bench_mfma_probe(1, 65, None, None) == -1
+    assert not hasattr(pkg.load_library(), "bench_mfma_probe")
+    assert not any("probe" in n for n in _declared_functions())
+
+
 FAKE = ctypes.c_void_p(0x10000)   # never dereferenced: every call below fails validation first
 
 
